@@ -1,0 +1,148 @@
+/*
+ * swiftprune.h - C ABI of the SwiftPrune per-layer pruning path for AMD gfx950.
+ *
+ * Method: "SwiftPrune: Hessian-Free Weight Pruning for Large Language Models"
+ * (arXiv 2501.16376).  One linear layer  y = W x  with  W[out, in]  is pruned
+ * from calibration activations  X[tokens, in]  in four steps:
+ *
+ *   1. statistics   xsq[q] = sum_t X[t,q]^2,  S = sum_q xsq[q]      (Algorithm 1, first statement)
+ *   2. score        L[r,q] = 1/2 * W[r,q]^2 / (1 - xsq[q]/S)         (Sec. 3.1, the score equation)
+ *   3. selection    per row, an EWMA threshold walk (Sec. 3.2, Algorithm 1 loop),
+ *                   or N:M group selection (Sec. 3.3)
+ *   4. apply        pruned weights are set to zero in place           (Algorithm 1, "w_i = 0")
+ *
+ * Conventions shared by every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller; the only
+ *     host pointers are `params` and the out-arguments of the host helpers.
+ *     The library allocates nothing, frees nothing and keeps no state.
+ *   - Matrices are row-major; `ld*` is the row pitch in ELEMENTS (>= columns).
+ *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL =
+ *     the default stream) and the call returns without synchronising.
+ *   - Return value: SP_OK (0) or a negative sp_status.  Arguments are checked
+ *     on the host before anything is launched; on error nothing was enqueued.
+ *   - Keep mask format: uint32 words, `mask_words = (in + 31) / 32` per row,
+ *     weight (r, q) is bit (q & 31) of word  r * mask_words + (q >> 5);
+ *     1 = keep, 0 = prune; bits at q >= in are written as 0.
+ */
+#ifndef SWIFTPRUNE_H
+#define SWIFTPRUNE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { SP_F32 = 0, SP_BF16 = 1 } sp_dtype;
+
+typedef enum {
+    SP_OK = 0,
+    SP_EINVAL = -1, /* bad argument (null pointer, non-positive size, pitch < columns, unknown dtype or pattern, ...) */
+    SP_ENOSPC = -2, /* workspace smaller than swiftprune_stats_workspace_bytes() */
+    SP_EHIP = -3    /* the HIP runtime refused a launch; hipGetLastError() has the code */
+} sp_status;
+
+/* EWMA parameters of Algorithm 1.  alpha, beta in (0, 1];  la is the
+ * threshold multiplier (the table "parameter adjustment under different
+ * pruning ratios" maps ratios to la).  The paper's only numeric alpha/beta is
+ * 0.125 (Sec. 4.2).  If la is NaN it is looked up from `sparsity`. */
+typedef struct {
+    float alpha;
+    float beta;
+    float la;
+} sp_ewma_params;
+
+/* flags of the select entry points */
+#define SP_SEQUENTIAL_ORDER 1u /* walk each row element by element in Algorithm 1's statement order, one
+                                  rounding per operation, no fused multiply-add: reproduces a sequential
+                                  fp32 evaluation bit for bit (slow; validation) */
+#define SP_APPLY_INPLACE 2u    /* also zero the pruned weights of W in place (step 4 fused in) */
+
+/*
+ * Step 1 (Algorithm 1, first statement; Sec. 3.1 "S is the sum of all x_i^2").
+ *
+ *   X          [tokens, in], pitch ldx, dtype dt               (device, read)
+ *   xsq        [in] fp32: accumulate == 0 -> overwritten with sum_t X[t,q]^2;
+ *              accumulate != 0 -> that sum is ADDED to the values already there
+ *              (so X may arrive in token chunks)              (device, read/write)
+ *   S, hr      written only when finalize != 0:  S[0] = sum_q xsq[q],
+ *              hr[q] = 0.5 / (1 - xsq[q]/S)  (per-channel factor of the score).
+ *              S == 0 gives hr = 0.5; a denominator <= 0 is replaced by FLT_EPSILON.
+ *              May be NULL when finalize == 0.                 (device, write)
+ *   workspace  >= swiftprune_stats_workspace_bytes(tokens, in) bytes, 256-byte
+ *              aligned, contents irrelevant on entry, clobbered (device)
+ *
+ * Sums run in fp32 over chains of at most a few hundred terms and are then
+ * combined in fp64 in a fixed order: the result does not depend on scheduling.
+ * Fast path: X 16-byte aligned, ldx and in multiples of 16 bytes worth of
+ * elements; anything else takes an element-wise path with the same result.
+ */
+int swiftprune_layer_stats(const void *X, int64_t tokens, int64_t in, int64_t ldx, sp_dtype dt,
+                           float *xsq, float *S, float *hr, int accumulate, int finalize,
+                           void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Steps 2+3, unstructured (Sec. 3.1 score equation; Sec. 3.2; Algorithm 1 loop body).
+ * Per row, q ascending, state est = L_0, dev = 0:
+ *     prune (r,q)  iff  L < est - la*dev      (state before q, strict)
+ *     est <- (1-alpha) est + alpha L ;  dev <- (1-beta) dev + beta |est - L|   (updated est)
+ * The sum S is held fixed during the walk (the paper's "S - w_i^2" update is
+ * below fp32 resolution of S for calibration sums).
+ *
+ *   W           [out, in], pitch ldw, dtype dt  (device; read, and written when SP_APPLY_INPLACE)
+ *   hr          [in] fp32 from swiftprune_layer_stats             (device, read)
+ *   sparsity    target pruning ratio; only used to look up la when params->la is NaN
+ *   params      host pointer; NULL = {0.125, 0.125, la from sparsity}
+ *   keep_mask   [out, (in+31)/32] uint32, fully overwritten        (device, write)
+ *   row_pruned  nullable [out] int32: number pruned in each row    (device, write)
+ *   scores      nullable [out, in] fp32: L, for validation         (device, write)
+ *   flags       SP_SEQUENTIAL_ORDER | SP_APPLY_INPLACE
+ *
+ * Default (scan) path: est/dev are evaluated as wavefront-wide linear-recurrence
+ * scans; they differ from a sequential fp32 walk by a few ulp, so a decision
+ * can differ only where L is within rounding of its threshold.
+ */
+int swiftprune_score_select(const void *W, int64_t out, int64_t in, int64_t ldw, sp_dtype dt,
+                            const float *hr, float sparsity, const sp_ewma_params *params,
+                            uint32_t *keep_mask, int32_t *row_pruned, float *scores,
+                            uint32_t flags, void *hip_stream);
+
+/*
+ * Steps 2+3, structured N:M (Sec. 3.3): in every group of m_group consecutive
+ * inputs of a row keep the n_keep entries of highest score and prune the rest;
+ * among equal scores the lower index is pruned first.  Supported: m_group in
+ * {4, 8, 16}, 0 < n_keep < m_group, in % m_group == 0 (else SP_EINVAL).
+ * Arguments as for swiftprune_score_select; flags: SP_APPLY_INPLACE.
+ * Deterministic and order-free: with equal hr the mask is unique.
+ */
+int swiftprune_nm_select(const void *W, int64_t out, int64_t in, int64_t ldw, sp_dtype dt,
+                         const float *hr, int n_keep, int m_group,
+                         uint32_t *keep_mask, float *scores, uint32_t flags, void *hip_stream);
+
+/*
+ * Step 4 (Algorithm 1: pruned w_i = 0, output C = W): W[r,q] <- +0 where the keep
+ * bit is 0; kept weights are left bit for bit.  W is modified in place.
+ */
+int swiftprune_apply(void *W, int64_t out, int64_t in, int64_t ldw, sp_dtype dt,
+                     const uint32_t *keep_mask, void *hip_stream);
+
+/* ---- host helpers (no device work) ---- */
+
+/* la for a pruning ratio from the paper's table (0.9 -> -1.5, 0.8 -> -0.9, 0.7 -> -0.2,
+ * 0.6 -> 0.2, 0.5 -> 0.5), piecewise linear between entries.  SP_EINVAL outside [0.5, 0.9]. */
+int swiftprune_la_for_sparsity(float sparsity, float *la);
+
+/* Bytes of workspace swiftprune_layer_stats needs for this shape (0 on bad arguments). */
+size_t swiftprune_stats_workspace_bytes(int64_t tokens, int64_t in);
+
+/* Static description of a status code. */
+const char *swiftprune_strerror(int code);
+
+/* Library version, "major.minor.patch". */
+const char *swiftprune_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SWIFTPRUNE_H */

@@ -1,0 +1,243 @@
+/*
+ * CPU oracle for the SwiftPrune per-layer pruning path.
+ *
+ * TEST INFRASTRUCTURE ONLY: a plain, slow, single-threaded statement of what
+ * the method computes, used by the tests, the smoke check and the CPU-baseline
+ * leg of the benchmark.  It shares no code with the HIP library and the
+ * product path never calls it.
+ *
+ * Source of every step: "SwiftPrune: Hessian-Free Weight Pruning for Large
+ * Language Models" (arXiv 2501.16376) - Sec. 3.1 (contribution score, the
+ * state-update table), Algorithm 1, Sec. 3.2 (EWMA), Sec. 3.3 (N:M).
+ *
+ * Precision: calibration statistics are accumulated in double and rounded to
+ * float once; the selection walk is provided in float (the precision the
+ * decisions are defined in for parity) and in double (for closed-form pins).
+ * Build with:  gcc -O2 -ffp-contract=off -fno-fast-math -shared -fPIC
+ *
+ * Pins (tests, CPU only): closed forms of the two recurrences, constant/step
+ * inputs, a hand-worked row, threshold monotonicity, scale and permutation
+ * invariances, reduction of N:M to per-group magnitude top-N under uniform
+ * channel energy, per-group exact sort, the rank-one inverse identity behind
+ * the score, statistics against a library sum.
+ * Parity unpinned (the paper gives no value that fixes them): the reading
+ * "x_q^2 is summed over all calibration tokens", the N:M ranking key and
+ * tie-break, the degenerate-input conventions (S == 0, 1 - x_q^2/S <= 0).
+ */
+#include <float.h>
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { ORC_F32 = 0, ORC_BF16 = 1 };
+
+/* bf16 is the upper half of an IEEE binary32. */
+static inline float bf16_to_f32(uint16_t b)
+{
+    uint32_t u = (uint32_t)b << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return f;
+}
+
+static inline float load_elem(const void *base, int64_t idx, int dt)
+{
+    if (dt == ORC_BF16)
+        return bf16_to_f32(((const uint16_t *)base)[idx]);
+    return ((const float *)base)[idx];
+}
+
+/* ------------------------------------------------------------------ */
+/* Step 1: calibration statistics (Algorithm 1, first statement;        */
+/* Sec. 3.1 "S is the sum of all x_i^2").                               */
+/* ------------------------------------------------------------------ */
+
+/*
+ * acc[q] += sum over t (ascending) of X[t,q]^2, in double.  X is
+ * [tokens, in] row-major with row pitch ldx (elements).  Calling it again with
+ * the next chunk of tokens continues the same sum.  With many calibration
+ * tokens x_q^2 is read as the q-th diagonal entry of X X^T (the paper's
+ * H = 2 X X^T), i.e. the SUM over tokens.
+ */
+void oracle_stats_accumulate(const void *X, int64_t tokens, int64_t in, int64_t ldx,
+                             int dt, double *acc)
+{
+    for (int64_t t = 0; t < tokens; ++t) {
+        for (int64_t q = 0; q < in; ++q) {
+            double x = (double)load_elem(X, t * ldx + q, dt);
+            acc[q] += x * x;
+        }
+    }
+}
+
+/*
+ * xsq[q] = (float)acc[q];  S = (float)(sum_q acc[q]) summed in double, q ascending.
+ */
+void oracle_stats_finalize(const double *acc, int64_t in, float *xsq, float *S)
+{
+    double s = 0.0;
+    for (int64_t q = 0; q < in; ++q) {
+        xsq[q] = (float)acc[q];
+        s += acc[q];
+    }
+    *S = (float)s;
+}
+
+/*
+ * Per-channel factor of the score:  hr[q] = 1/2 / (1 - xsq[q]/S)  (the score
+ * equation of Sec. 3.1 with w^2 taken out).  Float version: three roundings
+ * (divide, subtract, divide).
+ * Conventions where the paper is silent: S == 0 -> hr = 1/2 (score = w^2/2);
+ * a denominator that rounds to <= 0 is replaced by FLT_EPSILON.
+ */
+void oracle_channel_factor_f32(const float *xsq, float S, int64_t in, float *hr)
+{
+    for (int64_t q = 0; q < in; ++q) {
+        if (S == 0.0f) {
+            hr[q] = 0.5f;
+            continue;
+        }
+        float rho = xsq[q] / S;
+        float den = 1.0f - rho;
+        if (!(den > 0.0f))
+            den = FLT_EPSILON;
+        hr[q] = 0.5f / den;
+    }
+}
+
+/* Double version, straight from the double accumulators (no float rounding). */
+void oracle_channel_factor_f64(const double *acc, int64_t in, double *hr)
+{
+    double s = 0.0;
+    for (int64_t q = 0; q < in; ++q)
+        s += acc[q];
+    for (int64_t q = 0; q < in; ++q) {
+        if (s == 0.0) {
+            hr[q] = 0.5;
+            continue;
+        }
+        double den = 1.0 - acc[q] / s;
+        if (!(den > 0.0))
+            den = DBL_EPSILON;
+        hr[q] = 0.5 / den;
+    }
+}
+
+/* ------------------------------------------------------------------ */
+/* Steps 2-4: score, EWMA selection, N:M selection - float and double.  */
+/* ------------------------------------------------------------------ */
+
+#define REAL float
+#define FN(x) x##_f32
+#define FABS fabsf
+#include "ewma_body.inc"
+#undef REAL
+#undef FN
+#undef FABS
+
+#define REAL double
+#define FN(x) x##_f64
+#define FABS fabs
+#include "ewma_body.inc"
+#undef REAL
+#undef FN
+#undef FABS
+
+/* Scores of a whole layer, float: scores[r*in + q] = (w*w) * hr[q]. */
+void oracle_score_f32(const void *W, int64_t out, int64_t in, int64_t ldw, int dt,
+                      const float *hr, float *scores)
+{
+    for (int64_t r = 0; r < out; ++r)
+        score_row_f32(W, dt, r * ldw, in, hr, scores + r * in);
+}
+
+void oracle_score_f64(const void *W, int64_t out, int64_t in, int64_t ldw, int dt,
+                      const double *hr, double *scores)
+{
+    for (int64_t r = 0; r < out; ++r)
+        score_row_f64(W, dt, r * ldw, in, hr, scores + r * in);
+}
+
+/*
+ * Algorithm 1 exactly as printed, float: the sum S is part of the per-row
+ * state and loses w_i^2 whenever element i is pruned (third row of the
+ * state-update table), and the score is evaluated per element with the
+ * current S:  L_i = (0.5*w*w) / (1 - xsq[i]/S_r).
+ * Used as a cross-check of the fixed-S form above.  n_effective (nullable)
+ * receives how many of the subtractions changed the bits of S_r, summed over rows.
+ */
+void oracle_ewma_select_literal_f32(const void *W, int64_t out, int64_t in, int64_t ldw,
+                                    int dt, const float *xsq, float S,
+                                    float alpha, float beta, float la,
+                                    uint32_t *keep_mask, int32_t *row_pruned,
+                                    int64_t *n_effective)
+{
+    const int64_t words = (in + 31) / 32;
+    const float A = 1.0f - alpha;
+    const float B = 1.0f - beta;
+    int64_t eff = 0;
+    for (int64_t r = 0; r < out; ++r) {
+        float S_r = S;
+        float est = 0.0f, dev = 0.0f;
+        int32_t cnt = 0;
+        for (int64_t w = 0; w < words; ++w) keep_mask[r * words + w] = 0u;
+        for (int64_t i = 0; i < in; ++i) {
+            float w = load_elem(W, r * ldw + i, dt);
+            float w2 = w * w;
+            float half_w2 = 0.5f * w2;
+            float L;
+            if (S_r == 0.0f) {
+                L = half_w2;
+            } else {
+                float rho = xsq[i] / S_r;
+                float den = 1.0f - rho;
+                if (!(den > 0.0f))
+                    den = FLT_EPSILON;
+                L = half_w2 / den;
+            }
+            if (i == 0)
+                est = L;
+            float t = la * dev;
+            float thr = est - t;
+            if (L < thr) {
+                float S_new = S_r - w2;
+                if (S_new != S_r) ++eff;
+                S_r = S_new;
+                ++cnt;
+            } else {
+                keep_mask[r * words + (i >> 5)] |= (uint32_t)1 << (i & 31);
+            }
+            float a_est = A * est;
+            float a_new = alpha * L;
+            est = a_est + a_new;
+            float diff = est - L;
+            float b_dev = B * dev;
+            float b_new = beta * fabsf(diff);
+            dev = b_dev + b_new;
+        }
+        if (row_pruned) row_pruned[r] = cnt;
+    }
+    if (n_effective) *n_effective = eff;
+}
+
+/* ------------------------------------------------------------------ */
+/* Step 5: apply (Algorithm 1: w_i = 0 for pruned entries, c_i = w_i).  */
+/* ------------------------------------------------------------------ */
+
+/* W[r,q] <- +0 where the keep bit is 0; kept entries are left bit-for-bit. */
+void oracle_apply(void *W, int64_t out, int64_t in, int64_t ldw, int dt,
+                  const uint32_t *keep_mask)
+{
+    const int64_t words = (in + 31) / 32;
+    for (int64_t r = 0; r < out; ++r) {
+        for (int64_t q = 0; q < in; ++q) {
+            int keep = (keep_mask[r * words + (q >> 5)] >> (q & 31)) & 1u;
+            if (keep) continue;
+            if (dt == ORC_BF16)
+                ((uint16_t *)W)[r * ldw + q] = 0;
+            else
+                ((float *)W)[r * ldw + q] = 0.0f;
+        }
+    }
+}

@@ -1,0 +1,23 @@
+"""SwiftPrune per-layer pruning path for AMD MI355X (gfx950).
+
+The work is done by hand-written HIP kernels behind a C ABI
+(``include/swiftprune.h``, built into ``libswiftprune.so``); :mod:`.binding`
+marshals torch device tensors into those calls and :mod:`.synth` generates
+seeded synthetic layers.  There is no CPU fallback: calling an entry point
+without the built library or without a GPU raises.
+"""
+__version__ = "0.1.0"
+
+_BINDING_NAMES = (
+    "swiftprune_layer_stats", "swiftprune_score_select", "swiftprune_nm_select", "swiftprune_apply",
+    "swiftprune_la_for_sparsity", "swiftprune_stats_workspace_bytes", "swiftprune_strerror",
+    "swiftprune_version", "SwiftPruneError", "load_library", "prune_layer",
+    "SP_SEQUENTIAL_ORDER", "SP_APPLY_INPLACE", "SP_F32", "SP_BF16",
+)
+
+
+def __getattr__(name):
+    if name in _BINDING_NAMES:
+        from . import binding
+        return getattr(binding, name)
+    raise AttributeError(name)

@@ -1,0 +1,417 @@
+"""Pins of the CPU oracle: checks against what the paper and the mathematics fix.
+
+Every pin is a function ``pin_xxx(orc, L)`` where ``orc`` is the oracle package
+and ``L`` an (optionally different) loaded oracle library; it raises
+AssertionError when the library under test violates the pinned fact.  The same
+functions are run on the real oracle (must pass) and on deliberately broken
+copies of it (each must be caught by at least one pin).
+
+None of the pins restates the recurrence loop; they use closed forms, special
+inputs, invariants, library routines (numpy sort / inverse / sum) and a
+hand-worked example.
+"""
+from __future__ import annotations
+
+import os
+
+import numpy as np
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def _rng(seed):
+    return np.random.default_rng(seed)
+
+
+# ------------------------------------------------------------------ EWMA walk
+def pin_worked_rows(orc, L=None):
+    """Hand-worked rows (tests/golden/ewma_worked_rows.txt): bit-exact in both precisions."""
+    cases, cur = [], None
+    with open(os.path.join(GOLDEN, "ewma_worked_rows.txt")) as fh:
+        for line in fh:
+            line = line.split("#")[0].strip()
+            if not line:
+                continue
+            tok = line.split()
+            if tok[0] == "case":
+                cur = {"p": tuple(float(x) for x in tok[1:4]), "rows": []}
+                cases.append(cur)
+            else:
+                cur["rows"].append([float(x) for x in tok])
+    assert len(cases) >= 2
+    for c in cases:
+        rows = np.array(c["rows"])
+        a, b, la = c["p"]
+        for prec in ("f32", "f64"):
+            prune, est, dev = orc.ewma_row(rows[:, 0], a, b, la, precision=prec, L=L)
+            assert prune.tolist() == rows[:, 2].astype(int).tolist(), (c["p"], prec, prune)
+            assert np.array_equal(est.astype(np.float64), rows[:, 3]), (c["p"], prec, est)
+            assert np.array_equal(dev.astype(np.float64), rows[:, 4]), (c["p"], prec, dev)
+
+
+def closed_form_states(Lrow, alpha, beta):
+    """est/dev after each element from the closed-form sums (float64, no recurrence):
+       e_q = A^q L_0 + alpha * sum_{j=1..q} A^(q-j) L_j
+       d_q = beta * sum_{j=1..q} B^(q-j) |e_j - L_j|          (e_0 = L_0, d_0 = 0)
+    """
+    Lrow = np.asarray(Lrow, dtype=np.float64)
+    n = Lrow.shape[0]
+    A, B = 1.0 - alpha, 1.0 - beta
+    q = np.arange(n)
+    expo = q[:, None] - q[None, :]                      # q - j
+    lower = expo >= 0
+    PA = np.where(lower, np.power(A, np.where(lower, expo, 0)), 0.0)
+    PB = np.where(lower, np.power(B, np.where(lower, expo, 0)), 0.0)
+    src = alpha * Lrow
+    src[0] = Lrow[0]                                    # A^q L_0 term carries weight 1, not alpha
+    e = PA @ src
+    a = np.abs(e - Lrow)
+    a[0] = 0.0                                          # sum starts at j = 1
+    d = beta * (PB @ a)
+    return e, d
+
+
+def pin_closed_form(orc, L=None):
+    """Recurrence vs closed-form sums, and the decisions they imply."""
+    rng = _rng(11)
+    for (alpha, beta, la, n) in [(0.125, 0.125, 0.5, 96), (0.3, 0.07, -0.9, 64), (0.125, 0.25, 1.3, 130)]:
+        Lrow = rng.chisquare(1, size=n) * 3.0 + 1e-3
+        e, d = closed_form_states(Lrow, alpha, beta)
+        prune, est, dev = orc.ewma_row(Lrow, alpha, beta, la, precision="f64", L=L)
+        assert np.allclose(est, e, rtol=1e-12, atol=0), np.abs(est - e).max()
+        assert np.allclose(dev, d, rtol=1e-11, atol=1e-15), np.abs(dev - d).max()
+        # identity |e_j - L_j| = A |e_{j-1} - L_j|
+        assert np.allclose(np.abs(est[1:] - Lrow[1:]), (1 - alpha) * np.abs(est[:-1] - Lrow[1:]), rtol=1e-9)
+        # decisions from the closed-form state BEFORE each element
+        e_prev = np.concatenate([[Lrow[0]], e[:-1]])
+        d_prev = np.concatenate([[0.0], d[:-1]])
+        thr = e_prev - la * d_prev
+        safe = np.abs(Lrow - thr) > 1e-9 * np.maximum(np.abs(Lrow), np.abs(thr))
+        assert safe[1:].all()                         # element 0 sits exactly on its threshold (kept)
+        assert np.array_equal(prune.astype(bool), Lrow < thr)
+        assert 0 < prune.sum() < n
+        # float walk stays within rounding of the closed form
+        _, est32, dev32 = orc.ewma_row(Lrow, alpha, beta, la, precision="f32", L=L)
+        assert np.allclose(est32, e, rtol=2e-6), np.abs(est32 / e - 1).max()
+        assert np.allclose(dev32, d, rtol=1e-5, atol=1e-7)
+
+
+def pin_constant_row(orc, L=None):
+    """L constant -> est stays at it, dev stays 0, nothing is pruned whatever la is."""
+    for la in (-3.0, -0.2, 0.0, 0.5, 4.0):
+        for prec in ("f32", "f64"):
+            prune, est, dev = orc.ewma_row(np.full(50, 0.75), 0.125, 0.125, la, precision=prec, L=L)
+            assert prune.sum() == 0
+            assert np.all(est == 0.75) and np.all(dev == 0.0)
+
+
+def pin_first_two_elements(orc, L=None):
+    """Element 0 is never pruned; element 1 is pruned iff L_1 < L_0 for any la (dev is still 0)."""
+    rng = _rng(5)
+    for _ in range(200):
+        Lrow = rng.random(6) + 0.1
+        la = rng.uniform(-5, 5)
+        prune, _, _ = orc.ewma_row(Lrow, 0.125, 0.125, la, precision="f64", L=L)
+        assert prune[0] == 0
+        assert bool(prune[1]) == bool(Lrow[1] < Lrow[0])
+    # exact tie at element 1 is kept (strict inequality)
+    prune, _, _ = orc.ewma_row(np.array([2.0, 2.0, 1.0]), 0.125, 0.125, 0.0, precision="f32", L=L)
+    assert prune.tolist() == [0, 0, 1]
+
+
+def pin_monotone_in_la(orc, L=None):
+    """With S fixed the state does not depend on la: a larger la prunes a subset; la -> +inf prunes none
+    beyond what dev == 0 allows; la -> -inf prunes all elements after the first non-zero dev."""
+    rng = _rng(7)
+    Lrow = rng.chisquare(1, size=400)
+    prev = None
+    for la in (-4.0, -1.5, -0.9, -0.2, 0.2, 0.5, 1.0, 2.0, 8.0):
+        prune, _, _ = orc.ewma_row(Lrow, 0.125, 0.125, la, precision="f64", L=L)
+        p = prune.astype(bool)
+        if prev is not None:
+            assert not (p & ~prev).any(), la          # pruned(la2) subset of pruned(la1), la1 < la2
+        prev = p
+    big, _, _ = orc.ewma_row(Lrow, 0.125, 0.125, 1e9, precision="f64", L=L)
+    assert big[2:].sum() == 0                          # dev > 0 from element 1 on for generic input
+    small, _, _ = orc.ewma_row(Lrow, 0.125, 0.125, -1e9, precision="f64", L=L)
+    assert small[2:].sum() == Lrow.shape[0] - 2
+
+
+def pin_step_response(orc, L=None):
+    """L = c1 for q < k, c2 afterwards:  e_{k+m} = c2 + (c1 - c2) A^(m+1)."""
+    c1, c2, k, alpha = 5.0, 1.0, 10, 0.125
+    Lrow = np.concatenate([np.full(k, c1), np.full(40, c2)])
+    _, est, dev = orc.ewma_row(Lrow, alpha, 0.3, 0.5, precision="f64", L=L)
+    m = np.arange(40)
+    assert np.allclose(est[k:], c2 + (c1 - c2) * (1 - alpha) ** (m + 1), rtol=1e-13)
+    assert np.all(est[:k] == c1) and np.all(dev[:k] == 0)
+    # first deviation sample after the step: dev_k = beta * |e_k - c2|
+    assert np.isclose(dev[k], 0.3 * abs(est[k] - c2), rtol=1e-14)
+
+
+# ------------------------------------------------------------------ statistics and score
+def pin_stats_library_sum(orc, L=None):
+    """Step 1 against numpy's float64 column sum; bf16 and fp32 inputs, with a row pitch."""
+    from paper_2501_16376_amd import synth
+    rng = _rng(3)
+    X = (rng.standard_normal((300, 72)) * rng.lognormal(0, 0.5, 72)).astype(np.float32)
+    Xp = np.zeros((300, 80), dtype=np.float32)
+    Xp[:, :72] = X
+    Xp[:, 72:] = 1e6                                    # must be ignored (pitch > in)
+    acc = orc.stats_accumulate(Xp[:, :72], L=L)
+    ref = np.square(X.astype(np.float64)).sum(0)
+    assert np.allclose(acc, ref, rtol=1e-14)
+    # chunked accumulation continues the same sums
+    acc2 = orc.stats_accumulate(Xp[:100, :72], L=L)
+    acc2 = orc.stats_accumulate(Xp[100:, :72], acc2, L=L)
+    assert np.allclose(acc2, ref, rtol=1e-14)
+    xsq, S = orc.stats_finalize(acc, L=L)
+    assert np.array_equal(xsq, ref.astype(np.float32)) or np.allclose(xsq, ref, rtol=1e-7)
+    assert np.isclose(S, ref.sum(), rtol=1e-7)
+    # bf16 bits are widened exactly
+    Xb = synth.f32_to_bf16_bits(X)
+    accb = orc.stats_accumulate(Xb, L=L)
+    refb = np.square(synth.bf16_bits_to_f32(Xb).astype(np.float64)).sum(0)
+    assert np.allclose(accb, refb, rtol=1e-14)
+    # all-ones input: xsq = T, S = T*in, hr = 0.5/(1 - 1/in) (all exactly representable for in = 64)
+    ones = np.ones((128, 64), dtype=np.float32)
+    xsq1, S1, hr1 = orc.layer_stats(ones, L=L)
+    assert np.all(xsq1 == 128.0) and S1 == 128.0 * 64
+    assert np.all(hr1 == np.float32(0.5) / (np.float32(1) - np.float32(1 / 64)))
+
+
+def pin_inverse_identity(orc, L=None):
+    """The score's denominator is the paper's surrogate for the diagonal of the damped inverse Hessian.
+
+    For one activation vector x (n entries), H = 2 x x^T + (2S/n) I.  Sec. 3.1 derives
+        inv(H)_qq = (S/n + S - x_q^2) / ((2S/n)(S/n + S))
+                  = (1 - x_q^2/S) * G_q,   G_q = n/(2(1+n)) / (S - x_q^2) + n^2 / (2 S (1+n)).
+    So  0.5 * G_q / inv(H)_qq  must equal the oracle's channel factor 0.5/(1 - x_q^2/S), with inv(H)
+    from numpy.linalg.inv.  Also G_q -> n/(2S) when S >> x_q^2.
+    """
+    rng = _rng(9)
+    for n in (4, 9, 16):
+        x = rng.standard_normal(n) * rng.lognormal(0, 0.5, n)
+        S = float(np.sum(x * x))
+        H = 2.0 * np.outer(x, x) + (2.0 * S / n) * np.eye(n)
+        Hinv_qq = np.diag(np.linalg.inv(H))
+        closed = (S / n + S - x * x) / ((2 * S / n) * (S / n + S))
+        assert np.allclose(Hinv_qq, closed, rtol=1e-10)
+        G = n / (2.0 * (1 + n)) / (S - x * x) + n * n / (2.0 * S * (1 + n))
+        acc = orc.stats_accumulate(np.ascontiguousarray(x[None, :], dtype=np.float32), L=L)
+        x32 = x.astype(np.float32).astype(np.float64)
+        S32 = float(np.sum(x32 * x32))
+        H32 = 2.0 * np.outer(x32, x32) + (2.0 * S32 / n) * np.eye(n)
+        G32 = n / (2.0 * (1 + n)) / (S32 - x32 * x32) + n * n / (2.0 * S32 * (1 + n))
+        hr64 = orc.channel_factor_f64(acc, L=L)
+        assert np.allclose(hr64, 0.5 * G32 / np.diag(np.linalg.inv(H32)), rtol=1e-9)
+        # score = w^2 * hr
+        w = rng.standard_normal((3, n)).astype(np.float32)
+        sc = orc.score(w, hr64, precision="f64", L=L)
+        assert np.allclose(sc, 0.5 * w.astype(np.float64) ** 2 / (1.0 - x32 * x32 / S32), rtol=1e-12)
+    # large n: G_q / (n/(2S)) -> 1
+    n = 4096
+    x = rng.standard_normal(n)
+    S = float(np.sum(x * x))
+    G = n / (2.0 * (1 + n)) / (S - x * x) + n * n / (2.0 * S * (1 + n))
+    assert np.abs(G / (n / (2 * S)) - 1).max() < 5e-3
+
+
+def pin_float_factor_matches_double(orc, L=None):
+    """Float channel factor and float scores are the double ones to rounding; degenerate conventions."""
+    from paper_2501_16376_amd import synth
+    W, X = synth.config1()
+    acc = orc.stats_accumulate(X, L=L)
+    xsq, S = orc.stats_finalize(acc, L=L)
+    hr32 = orc.channel_factor_f32(xsq, S, L=L)
+    hr64 = orc.channel_factor_f64(acc, L=L)
+    assert np.allclose(hr32, hr64, rtol=3e-7)
+    assert hr32.min() >= 0.5 and hr32.max() > 0.6       # outlier channels raise the factor
+    s32 = orc.score(W, hr32, precision="f32", L=L)
+    s64 = orc.score(W, hr64, precision="f64", L=L)
+    assert np.allclose(s32, s64, rtol=5e-7)
+    # conventions where the paper is silent
+    assert np.all(orc.channel_factor_f32(np.zeros(8, np.float32), 0.0, L=L) == 0.5)
+    one_hot = np.zeros(8, np.float32)
+    one_hot[3] = 4.0
+    hr = orc.channel_factor_f32(one_hot, 4.0, L=L)
+    assert hr[3] == np.float32(0.5) / np.finfo(np.float32).eps and np.all(np.delete(hr, 3) == 0.5)
+
+
+# ------------------------------------------------------------------ whole-layer selection
+def pin_select_metamorphic(orc, L=None):
+    """Scaling W or X by a power of two, permuting rows: masks follow exactly."""
+    from paper_2501_16376_amd import synth
+    W, X = synth.layer_inputs(24, 160, 64, seed=4, dtype="f32", n_outlier=2)
+    _, _, hr = orc.layer_stats(X, L=L)
+    m0, c0, s0 = orc.ewma_select(W, hr, 0.125, 0.125, 0.5, want_scores=True, L=L)
+    assert 0.3 < c0.sum() / W.size < 0.7
+    # W * 2^k: scores scale by 4^k exactly, decisions unchanged
+    m1, c1, s1 = orc.ewma_select(W * np.float32(8.0), hr, 0.125, 0.125, 0.5, want_scores=True, L=L)
+    assert np.array_equal(m0, m1) and np.array_equal(s1, s0 * np.float32(64.0))
+    # X * 2^k: xsq and S scale by 4^k, the ratio (and hr) is unchanged bit for bit
+    _, _, hr2 = orc.layer_stats(X * np.float32(4.0), L=L)
+    assert np.array_equal(hr, hr2)
+    # row permutation
+    perm = _rng(1).permutation(W.shape[0])
+    m2, c2, _ = orc.ewma_select(np.ascontiguousarray(W[perm]), hr, 0.125, 0.125, 0.5, L=L)
+    assert np.array_equal(m2, m0[perm]) and np.array_equal(c2, c0[perm])
+    # token permutation leaves the statistics unchanged up to double rounding
+    xsq_a, S_a, _ = orc.layer_stats(X, L=L)
+    xsq_b, S_b, _ = orc.layer_stats(np.ascontiguousarray(X[_rng(2).permutation(X.shape[0])]), L=L)
+    assert np.allclose(xsq_a, xsq_b, rtol=1e-7) and np.isclose(S_a, S_b, rtol=1e-7)
+    # mask format: bit (q & 31) of word q >> 5; row counts match the mask; pad bits are zero
+    keep = orc.unpack_mask(m0, W.shape[1])
+    assert np.array_equal((~keep).sum(1), c0)
+    assert keep[:, 0].all()
+    row0 = s0[0]
+    prune0, _, _ = orc.ewma_row(row0, 0.125, 0.125, 0.5, precision="f32", L=L)
+    for q in (0, 1, 31, 32, 33, 100, 159):
+        assert ((int(m0[0, q >> 5]) >> (q & 31)) & 1) == (0 if prune0[q] else 1)
+    W2, X2 = synth.layer_inputs(3, 40, 16, seed=8, dtype="f32", n_outlier=1)
+    _, _, hrb = orc.layer_stats(X2, L=L)
+    mb, _, _ = orc.ewma_select(W2, hrb, 0.125, 0.125, 0.5, L=L)
+    assert mb.shape == (3, 2) and np.all((mb[:, 1] >> 8) == 0)
+    # pitch: a wider parent array gives the same result
+    Wp = np.full((24, 200), 7.0, dtype=np.float32)
+    Wp[:, :160] = W
+    m3, _, _ = orc.ewma_select(Wp[:, :160], hr, 0.125, 0.125, 0.5, L=L)
+    assert np.array_equal(m3, m0)
+
+
+def pin_uniform_energy_reduces_to_magnitude(orc, L=None):
+    """Equal channel energies -> score proportional to w^2: N:M equals per-group top-N of |w|, and the
+    EWMA selection equals the walk over c*w^2."""
+    rng = _rng(21)
+    n, out = 64, 12
+    X = rng.choice([-1.0, 1.0], size=(32, n)).astype(np.float32)       # xsq[q] = 32 for all q
+    xsq, S, hr = orc.layer_stats(X, L=L)
+    assert np.all(xsq == 32.0) and np.all(hr == hr[0])
+    W = rng.standard_normal((out, n)).astype(np.float32)
+    for (nk, m) in [(2, 4), (4, 8), (1, 4), (3, 4), (2, 8), (8, 16)]:
+        mask, _ = orc.nm_select(W, hr, nk, m, L=L)
+        keep = orc.unpack_mask(mask, n)
+        mag = np.abs(W).reshape(out, n // m, m)
+        order = np.argsort(mag, axis=2, kind="stable")                 # library sort: ascending |w|
+        ref = np.ones_like(mag, dtype=bool)
+        np.put_along_axis(ref, order[:, :, : m - nk], False, axis=2)
+        assert np.array_equal(keep, ref.reshape(out, n)), (nk, m)
+    mask, cnt, sc = orc.ewma_select(W, hr, 0.125, 0.125, 0.2, want_scores=True, L=L)
+    for r in range(out):
+        prune, _, _ = orc.ewma_row((W[r] * W[r]) * hr[0], 0.125, 0.125, 0.2, precision="f32", L=L)
+        assert np.array_equal(~orc.unpack_mask(mask, n)[r], prune.astype(bool))
+
+
+def pin_nm_invariants(orc, L=None):
+    """Exactly M-N pruned per group; every kept score >= every pruned one; equals a per-group
+    lexicographic sort on (score, index); ties prune the lower index first."""
+    from paper_2501_16376_amd import synth
+    Wb, Xb = synth.layer_inputs(16, 96, 64, seed=6, dtype="bf16", n_outlier=3)
+    _, _, hr = orc.layer_stats(Xb, L=L)
+    for (nk, m) in [(2, 4), (4, 8), (1, 4), (3, 4), (6, 8), (4, 16)]:
+        mask, sc = orc.nm_select(Wb, hr, nk, m, want_scores=True, L=L)
+        keep = orc.unpack_mask(mask, 96).reshape(16, 96 // m, m)
+        assert np.all(keep.sum(2) == nk)
+        g = sc.reshape(16, 96 // m, m)
+        kept_min = np.where(keep, g, np.inf).min(2)
+        pruned_max = np.where(~keep, g, -np.inf).max(2)
+        assert np.all(kept_min >= pruned_max)
+        idx = np.broadcast_to(np.arange(m), g.shape)
+        ref = np.ones_like(keep)
+        for r in range(16):
+            for j in range(96 // m):
+                order = np.lexsort((idx[r, j], g[r, j]))               # by score, then index
+                ref[r, j, order[: m - nk]] = False
+        assert np.array_equal(keep, ref), (nk, m)
+    # ties: all-equal weights, equal energies -> the first M-N of each group go
+    X = np.ones((4, 16), dtype=np.float32)
+    _, _, hr1 = orc.layer_stats(X, L=L)
+    mask, _ = orc.nm_select(np.full((2, 16), 0.5, np.float32), hr1, 2, 4, L=L)
+    assert np.array_equal(orc.unpack_mask(mask, 16), np.tile([False, False, True, True], (2, 4)))
+    mask, _ = orc.nm_select(np.full((1, 16), 0.5, np.float32), hr1, 3, 8, L=L)
+    assert np.array_equal(orc.unpack_mask(mask, 16)[0], np.tile([False] * 5 + [True] * 3, 2))
+
+
+def pin_channel_energy_changes_ranking(orc, L=None):
+    """A weight on a high-energy channel outranks a slightly larger weight on a quiet channel."""
+    X = np.ones((8, 4), dtype=np.float32)
+    X[:, 2] = 3.0                                        # xsq = [8, 8, 72, 8], S = 96
+    _, _, hr = orc.layer_stats(X, L=L)
+    assert hr[2] == np.float32(0.5) / (np.float32(1) - np.float32(72) / np.float32(96))   # = 2.0
+    W = np.array([[1.0, 1.2, 0.9, 1.1]], dtype=np.float32)
+    mask, sc = orc.nm_select(W, hr, 2, 4, want_scores=True, L=L)
+    # quiet channels: 0.5/(1 - 8/96) = 6/11; loud channel: 2 -> scores [6/11, 1.44*6/11, 1.62, 1.21*6/11]
+    assert orc.unpack_mask(mask, 4)[0].tolist() == [False, True, True, False]
+    assert np.allclose(sc[0], [6 / 11, 1.44 * 6 / 11, 1.62, 1.21 * 6 / 11], rtol=1e-6)
+
+
+def pin_literal_form(orc, L=None):
+    """Algorithm 1 as printed (S shrinks by w^2 on pruning) vs the fixed-S form: identical for
+    calibration-sized sums, different when S is comparable to w^2."""
+    from paper_2501_16376_amd import synth
+    W, X = synth.config1()
+    xsq, S, hr = orc.layer_stats(X, L=L)
+    m0, c0, _ = orc.ewma_select(W, hr, 0.125, 0.125, 0.5, L=L)
+    m1, c1, eff = orc.ewma_select_literal(W, xsq, S, 0.125, 0.125, 0.5, L=L)
+    assert eff == 0 and np.array_equal(m0, m1) and np.array_equal(c0, c1)
+    assert float(np.max(W * W)) < float(np.spacing(np.float32(S))) / 2
+    # tiny activations: S ~ w^2, so the update matters and the sum really moves
+    Xs = (X * np.float32(1e-4))[:4]
+    xsq_s, S_s, hr_s = orc.layer_stats(Xs, L=L)
+    m2, _, _ = orc.ewma_select(W, hr_s, 0.125, 0.125, 0.5, L=L)
+    m3, _, eff3 = orc.ewma_select_literal(W, xsq_s, S_s, 0.125, 0.125, 0.5, L=L)
+    assert eff3 > 1000 and not np.array_equal(m2, m3)
+
+
+def pin_apply(orc, L=None):
+    from paper_2501_16376_amd import synth
+    Wb, Xb = synth.layer_inputs(8, 72, 32, seed=12, dtype="bf16", n_outlier=1)
+    _, _, hr = orc.layer_stats(Xb, L=L)
+    mask, cnt, _ = orc.ewma_select(Wb, hr, 0.125, 0.125, 0.5, L=L)
+    keep = orc.unpack_mask(mask, 72)
+    out = orc.apply(Wb.copy(), mask, L=L)
+    assert np.array_equal(out[keep], Wb[keep]) and np.all(out[~keep] == 0)
+    Wf = synth.bf16_bits_to_f32(Wb)
+    Wf[0, 0] = -0.0
+    outf = orc.apply(Wf.copy(), mask, L=L)
+    assert np.array_equal(outf[keep].view(np.uint32), Wf[keep].view(np.uint32))
+    assert np.all(outf[~keep].view(np.uint32) == 0)
+    # pitch is honoured and the padding is untouched
+    Wp = np.full((8, 80), 0x3F80, dtype=np.uint16)
+    Wp[:, :72] = Wb
+    orc.apply(Wp[:, :72], mask, L=L)
+    assert np.all(Wp[:, 72:] == 0x3F80) and np.array_equal(Wp[:, :72], out)
+
+
+def pin_sort_comparator(orc, L=None):
+    """The EWMA rule stands in for 'sort the scores and drop the smallest' (Sec. 3.1): with k = the
+    number EWMA prunes in a row, most of them are among the k smallest scores; and the la table of the
+    paper orders the achieved sparsity.  Returns the measured numbers for reporting."""
+    from paper_2501_16376_amd import synth
+    W, X = synth.config1()
+    _, _, hr = orc.layer_stats(X, L=L)
+    report = {}
+    prev = 1.0
+    for ratio, la in [(0.9, -1.5), (0.8, -0.9), (0.7, -0.2), (0.6, 0.2), (0.5, 0.5)]:
+        mask, cnt, sc = orc.ewma_select(W, hr, 0.125, 0.125, la, want_scores=True, L=L)
+        pruned = ~orc.unpack_mask(mask, W.shape[1])
+        inter = 0
+        for r in range(W.shape[0]):
+            k = int(cnt[r])
+            smallest = np.argsort(sc[r], kind="stable")[:k]
+            inter += int(pruned[r, smallest].sum())
+        overlap = inter / max(1, int(cnt.sum()))
+        achieved = cnt.sum() / W.size
+        report[ratio] = (la, float(achieved), float(overlap))
+        assert achieved < prev                        # lower table ratio -> fewer pruned
+        assert abs(achieved - ratio) < 0.1            # synthetic Gaussian weights land near the table
+        assert overlap > 0.85
+        prev = achieved
+    return report
+
+
+ALL_PINS = [pin_worked_rows, pin_closed_form, pin_constant_row, pin_first_two_elements,
+            pin_monotone_in_la, pin_step_response, pin_stats_library_sum, pin_inverse_identity,
+            pin_float_factor_matches_double, pin_select_metamorphic,
+            pin_uniform_energy_reduces_to_magnitude, pin_nm_invariants,
+            pin_channel_energy_changes_ranking, pin_literal_form, pin_apply, pin_sort_comparator]

@@ -1,0 +1,71 @@
+"""CPU-only: every deliberately broken copy of the oracle must be caught by at least one pin.
+
+The mistakes are planted in a temporary copy of the oracle's source text (never in the tree, never
+on the GPU), compiled with the oracle's own flags and run through tests/pins.py."""
+import os
+import shutil
+
+import pytest
+
+import pins
+
+# (name, file, text to replace, replacement)
+MUTANTS = [
+    ("dev_uses_old_est", "ewma_body.inc", "est = a_est + a_new;\n        REAL diff = est - L[q];",
+     "REAL diff = est - L[q];\n        est = a_est + a_new;"),
+    ("non_strict_compare", "ewma_body.inc", "(L[q] < thr)", "(L[q] <= thr)"),
+    ("threshold_sign", "ewma_body.inc", "REAL thr = est - t;", "REAL thr = est + t;"),
+    ("alpha_beta_swapped_est", "ewma_body.inc", "REAL a_new = alpha * L[q];", "REAL a_new = beta * L[q];"),
+    ("alpha_beta_swapped_dev", "ewma_body.inc", "REAL b_new = beta * FABS(diff);", "REAL b_new = alpha * FABS(diff);"),
+    ("est_not_initialised_to_L0", "ewma_body.inc", "if (q == 0)\n            est = L[0];", ""),
+    ("decay_is_alpha", "ewma_body.inc", "const REAL A = one - alpha;", "const REAL A = alpha;"),
+    ("decay_b_is_alpha", "ewma_body.inc", "const REAL B = one - beta;", "const REAL B = one - alpha;"),
+    ("dev_no_abs", "ewma_body.inc", "beta * FABS(diff)", "beta * (diff)"),
+    ("decision_after_update", "ewma_body.inc",
+     "REAL t = la * dev;\n        REAL thr = est - t;\n        prune[q] = (uint8_t)(L[q] < thr);\n        REAL a_est = A * est;",
+     "REAL a_est = A * est;"),
+    ("score_not_squared", "ewma_body.inc", "REAL w2 = w * w;", "REAL w2 = FABS(w);"),
+    ("score_ignores_channel", "ewma_body.inc", "L[q] = w2 * hr[q];", "L[q] = w2 * hr[0];"),
+    ("nm_keeps_wrong_count", "ewma_body.inc", "if (rank >= m_group - n_keep)", "if (rank >= n_keep)"),
+    ("nm_tie_break_reversed", "ewma_body.inc", "L[g + p] == L[g + i] && p < i", "L[g + p] == L[g + i] && p > i"),
+    ("nm_keeps_smallest", "ewma_body.inc", "if (L[g + p] < L[g + i]) ++rank;", "if (L[g + p] > L[g + i]) ++rank;"),
+    ("mask_bit_order", "ewma_body.inc", "else keep_mask[r * words + (q >> 5)] |= (uint32_t)1 << (q & 31);",
+     "else keep_mask[r * words + (q >> 5)] |= (uint32_t)1 << (31 - (q & 31));"),
+    ("stats_not_squared", "swiftprune_oracle.c", "acc[q] += x * x;", "acc[q] += fabs(x);"),
+    ("stats_ignores_pitch", "swiftprune_oracle.c", "load_elem(X, t * ldx + q, dt)", "load_elem(X, t * in + q, dt)"),
+    ("factor_plus", "swiftprune_oracle.c", "float den = 1.0f - rho;\n        if (!(den > 0.0f))\n            den = FLT_EPSILON;\n        hr[q] = 0.5f / den;",
+     "float den = 1.0f + rho;\n        if (!(den > 0.0f))\n            den = FLT_EPSILON;\n        hr[q] = 0.5f / den;"),
+    ("factor_f64_no_half", "swiftprune_oracle.c", "hr[q] = 0.5 / den;", "hr[q] = 1.0 / den;"),
+    ("S_is_mean", "swiftprune_oracle.c", "*S = (float)s;", "*S = (float)(s / (double)in);"),
+    ("bf16_low_half", "swiftprune_oracle.c", "uint32_t u = (uint32_t)b << 16;", "uint32_t u = (uint32_t)b;"),
+    ("literal_never_updates_S", "swiftprune_oracle.c", "S_r = S_new;", ""),
+    ("apply_zeroes_kept", "swiftprune_oracle.c", "if (keep) continue;", "if (!keep) continue;"),
+]
+
+
+@pytest.fixture(scope="module")
+def src_dir(orc):
+    return os.path.dirname(os.path.abspath(orc.__file__))
+
+
+@pytest.mark.parametrize("mutant", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_mutant_is_caught(orc, src_dir, tmp_path, mutant):
+    name, fname, old, new = mutant
+    for f in ("swiftprune_oracle.c", "ewma_body.inc"):
+        shutil.copy(os.path.join(src_dir, f), tmp_path / f)
+    text = (tmp_path / fname).read_text()
+    assert text.count(old) >= 1, f"mutation site for {name} not found"
+    (tmp_path / fname).write_text(text.replace(old, new))
+    so = str(tmp_path / f"liboracle_{name}.so")
+    import subprocess
+    subprocess.run(["gcc", *[f for f in orc.CFLAGS if f not in ("-Wall", "-Wextra")],
+                    str(tmp_path / "swiftprune_oracle.c"), "-o", so, "-lm"], check=True)
+    L = orc.lib(so)
+    caught = []
+    for pin in pins.ALL_PINS:
+        try:
+            pin(orc, L)
+        except AssertionError:
+            caught.append(pin.__name__)
+    assert caught, f"no pin notices the planted mistake '{name}'"
+    print(f"{name}: caught by {', '.join(caught)}")
