@@ -1,0 +1,256 @@
+#!/usr/bin/env python3
+"""Benchmark of the SwiftPrune layer path on one MI355X.
+
+Workload (default): a Llama-3-8B-shaped stack, 32 decoder blocks x 7 linear layers, bf16 random
+weights, 128 x 2048 synthetic calibration tokens per layer input, 50 % unstructured (la = 0.5).
+One step = pruning the whole stack in place: per linear layer, calibration statistics
+(swiftprune_layer_stats) then score + EWMA selection with the apply fused in
+(swiftprune_score_select | SP_APPLY_INPLACE).  Everything is resident in HBM before timing starts;
+between steps the weights are restored from a pristine copy outside the timed region.
+
+Prints ONE JSON line: weights-pruned GB/s, ms per step, HBM-roofline numbers of the dominant kernel
+(measured with events on the launch stream inside the timed steps) and the CPU oracle's rate on a
+bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--blocks", type=int, default=32, help="decoder blocks in the stack (32 = the 8B shape)")
+    ap.add_argument("--model", default="llama3-8b", choices=["llama3-8b", "llama2-7b"])
+    ap.add_argument("--mode", default="unstructured", choices=["unstructured", "2:4", "4:8"])
+    ap.add_argument("--tokens", type=int, default=128 * 2048)
+    ap.add_argument("--shared-stats", action="store_true",
+                    help="compute statistics once per distinct layer input (q/k/v and gate/up share)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-events", action="store_true",
+                    help="do not bracket the statistics launches with events")
+    return ap.parse_args()
+
+
+# which activation feeds which layer of a block
+INPUT_OF = {"q": "attn_in", "k": "attn_in", "v": "attn_in", "o": "attn_out",
+            "gate": "mlp_in", "up": "mlp_in", "down": "mlp_mid"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (no collectives, no sharding); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2501_16376_amd import binding as sp, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    sp.load_library()
+
+    block = synth.LLAMA3_8B_BLOCK if args.model == "llama3-8b" else synth.LLAMA2_7B_BLOCK
+    T = args.tokens
+    nm = None if args.mode == "unstructured" else tuple(int(x) for x in args.mode.split(":"))
+    la = 0.5
+
+    # ---- resident data: activations per distinct layer input, weights per (block, layer)
+    t_setup = time.time()
+    widths = {INPUT_OF[name]: n for name, _, n in block}
+    X = {key: synth.device_activations(T, n, seed=1000 + i, device=dev)
+         for i, (key, n) in enumerate(sorted(widths.items()))}
+    weights, pristine = [], []
+    for bi in range(args.blocks):
+        for li, (name, out, n) in enumerate(block):
+            W = synth.device_weights(out, n, seed=10_000 + 16 * bi + li, device=dev)
+            pristine.append(W)
+            weights.append(W.clone())
+    layers = [(name, out, n) for _ in range(args.blocks) for (name, out, n) in block]
+    bufs = {}
+    for name, out, n in block:
+        if (out, n) not in bufs:
+            bufs[(out, n)] = sp.LayerBuffers(out, n, T, dev)
+    torch.cuda.synchronize()
+    setup_s = time.time() - t_setup
+
+    w_bytes = sum(out * n * 2 for _, out, n in layers)
+    n_weights = sum(out * n for _, out, n in layers)
+    stats_calls = [(name, n) for name, _, n in layers]
+    if args.shared_stats:
+        seen_per_block = []
+        stats_bytes = 0
+        for bi in range(args.blocks):
+            stats_bytes += sum(T * n * 2 for n in [widths[k] for k in sorted(widths)])
+    else:
+        stats_bytes = sum(T * n * 2 for _, n in stats_calls)
+    # select + apply fused: W read, W written, mask written, factor read
+    select_bytes = sum(out * n * 2 * 2 + out * n // 8 + n * 4 for _, out, n in layers)
+    algo_bytes = stats_bytes + select_bytes
+
+    stream = torch.cuda.current_stream()
+    ev_pairs = []       # (start, stop, bytes) around statistics launches of timed steps
+
+    def step(record):
+        idx = 0
+        for bi in range(args.blocks):
+            done_inputs = set()
+            for name, out, n in block:
+                W = weights[idx]
+                idx += 1
+                b = bufs[(out, n)]
+                key = INPUT_OF[name]
+                if not (args.shared_stats and key in done_inputs):
+                    if record:
+                        e0 = torch.cuda.Event(enable_timing=True)
+                        e1 = torch.cuda.Event(enable_timing=True)
+                        e0.record(stream)
+                    sp.swiftprune_layer_stats(X[key], b.xsq, b.S, b.hr, workspace=b.workspace, stream=stream)
+                    if record:
+                        e1.record(stream)
+                        ev_pairs.append((e0, e1, T * n * 2))
+                    done_inputs.add(key)
+                    if args.shared_stats:
+                        # keep the factor of this input for the layers that share it
+                        shared_hr[key].copy_(b.hr)
+                hr = shared_hr[key] if args.shared_stats else b.hr
+                if nm is None:
+                    sp.swiftprune_score_select(W, hr, b.keep_mask, la=la, row_pruned=b.row_pruned,
+                                               flags=sp.SP_APPLY_INPLACE, stream=stream)
+                else:
+                    sp.swiftprune_nm_select(W, hr, nm[0], nm[1], b.keep_mask, flags=sp.SP_APPLY_INPLACE,
+                                            stream=stream)
+
+    shared_hr = {key: torch.empty(n, dtype=torch.float32, device=dev) for key, n in widths.items()}
+
+    def restore():
+        for W, P in zip(weights, pristine):
+            W.copy_(P)
+
+    for _ in range(args.warmup):
+        restore()
+        step(False)
+    torch.cuda.synchronize()
+
+    step_events = []
+    t_wall0 = time.time()
+    for _ in range(args.steps):
+        restore()
+        torch.cuda.synchronize()
+        s0 = torch.cuda.Event(enable_timing=True)
+        s1 = torch.cuda.Event(enable_timing=True)
+        s0.record(stream)
+        step(not args.no_kernel_events)
+        s1.record(stream)
+        step_events.append((s0, s1))
+    torch.cuda.synchronize()
+    wall_s = time.time() - t_wall0
+    step_ms = [a.elapsed_time(b) for a, b in step_events]
+    ms_per_step = sum(step_ms) / len(step_ms)
+
+    # achieved sparsity of the last step (from the per-row counts of the last layer of each shape)
+    pruned_frac = None
+    if nm is None:
+        b = bufs[(block[-1][1], block[-1][2])]
+        pruned_frac = float(b.row_pruned.sum().item()) / (block[-1][1] * block[-1][2])
+
+    roofline = {"bound": "hbm", "kernel": "stats_partial_kernel (swiftprune_layer_stats)",
+                "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None, "traffic": None}
+    if ev_pairs:
+        tot_ms = sum(a.elapsed_time(b) for a, b, _ in ev_pairs)
+        tot_bytes = sum(nb for _, _, nb in ev_pairs)
+        ach = tot_bytes / (tot_ms * 1e-3) / 1e9
+        roofline.update(achieved=round(ach, 1), frac=round(ach / HBM_PEAK_GBS, 4),
+                        launches=len(ev_pairs), avg_launch_us=round(tot_ms * 1e3 / len(ev_pairs), 2),
+                        bytes_per_launch_avg=int(tot_bytes / len(ev_pairs)))
+
+    value = w_bytes / (ms_per_step * 1e-3) / 1e9
+    result = {
+        "metric": "GB/s of weights pruned (% of HBM peak); seconds to prune 8B-shaped model",
+        "value": round(value, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 3),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{args.model}-shaped stack, {args.blocks} blocks x 7 linear layers, bf16 W, "
+                               f"{T} calibration tokens per layer, "
+                               + ("50% unstructured (la=0.5)" if nm is None else f"{args.mode} structured"),
+                   "storage": "bf16", "tokens": T, "blocks": args.blocks, "mode": args.mode,
+                   "stats_calls_per_block": 4 if args.shared_stats else 7,
+                   "weights": n_weights},
+        "seconds_per_model": round(ms_per_step * 1e-3, 5),
+        "step_ms_min_max": [round(min(step_ms), 3), round(max(step_ms), 3)],
+        "algorithmic_bytes_per_step": int(algo_bytes),
+        "hbm_frac_whole_step": round(algo_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "achieved_sparsity_last_layer": pruned_frac,
+        "setup_s": round(setup_s, 1),
+        "timed_wall_s_incl_restore": round(wall_s, 3),
+        "roofline": roofline,
+        "paper_context": "LLaMA3.1-8B pruned in 9.49 s (50%) / 9.28 s (2:4) on 8x RTX 4090 (Table 3 of the paper); "
+                         "not the same machine, weights or calibration set",
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(block, X, pristine, T, nm, la)
+
+    print(json.dumps(result))
+
+
+def cpu_baseline(block, X, pristine, T, nm, la):
+    """The CPU oracle, as it stands, on a bounded sample: the first decoder block's layers with a
+    token sample of the calibration set; statistics time is scaled to the full token count."""
+    import numpy as np
+    import oracle
+    from paper_2501_16376_amd import synth
+
+    oracle.lib()
+    sample_T = min(T, 32768)
+    t_stats = 0.0
+    t_sel = 0.0
+    w_bytes = 0
+    for li, (name, out, n) in enumerate(block):
+        Xh = synth.torch_to_host_bits(X[INPUT_OF[name]][:sample_T])
+        Wh = synth.torch_to_host_bits(pristine[li])
+        t0 = time.perf_counter()
+        xsq, S, hr = oracle.layer_stats(Xh)
+        t1 = time.perf_counter()
+        if nm is None:
+            mask, _, _ = oracle.ewma_select(Wh, hr, 0.125, 0.125, la)
+        else:
+            mask, _ = oracle.nm_select(Wh, hr, nm[0], nm[1])
+        oracle.apply(Wh, mask)
+        t2 = time.perf_counter()
+        t_stats += (t1 - t0) * (T / sample_T)
+        t_sel += t2 - t1
+        w_bytes += out * n * 2
+    total = t_stats + t_sel
+    return {"value": round(w_bytes / total / 1e9, 5), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"one decoder block (7 layers, {w_bytes / 1e9:.3f} GB of weights); selection+apply on the "
+                      f"full matrices, statistics on the first {sample_T} of {T} tokens with the time scaled "
+                      f"by {T / sample_T:.0f}",
+            "seconds_per_block_scaled": round(total, 2),
+            "measured_cpu_seconds": round(t_stats * sample_T / T + t_sel, 2)}
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,215 @@
+"""ctypes binding of libswiftprune.so: argument marshalling only.
+
+Each function has the name and the argument order of its C entry point
+(include/swiftprune.h) and takes torch tensors living on the GPU; torch is used
+for device memory and for the current stream, nothing else.  Every step of the
+path runs in the HIP kernels.  There is no fallback: a missing library raises
+at first use.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import math
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libswiftprune.so")
+
+SP_F32, SP_BF16 = 0, 1
+SP_OK, SP_EINVAL, SP_ENOSPC, SP_EHIP = 0, -1, -2, -3
+SP_SEQUENTIAL_ORDER, SP_APPLY_INPLACE = 1, 2
+
+EXPORTS = ("swiftprune_layer_stats", "swiftprune_score_select", "swiftprune_nm_select",
+           "swiftprune_apply", "swiftprune_la_for_sparsity", "swiftprune_stats_workspace_bytes",
+           "swiftprune_strerror", "swiftprune_version")
+
+
+class SwiftPruneError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {swiftprune_strerror(code)} ({code})")
+
+
+class sp_ewma_params(C.Structure):
+    _fields_ = [("alpha", C.c_float), ("beta", C.c_float), ("la", C.c_float)]
+
+
+_lib = None
+
+
+def load_library(path: str | None = None) -> C.CDLL:
+    """Load the C-ABI library (no build is attempted here)."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    p = path or LIB_PATH
+    if not os.path.exists(p):
+        raise ImportError(f"{p} is missing: build it with `python -m paper_2501_16376_amd.build` "
+                          "(or __graft_entry__.build()); there is no CPU fallback")
+    L = C.CDLL(p)
+    vp, i64, i32, u32, f = C.c_void_p, C.c_int64, C.c_int, C.c_uint32, C.c_float
+    L.swiftprune_layer_stats.argtypes = [vp, i64, i64, i64, i32, vp, vp, vp, i32, i32, vp, C.c_size_t, vp]
+    L.swiftprune_layer_stats.restype = i32
+    L.swiftprune_score_select.argtypes = [vp, i64, i64, i64, i32, vp, f, C.POINTER(sp_ewma_params),
+                                          vp, vp, vp, u32, vp]
+    L.swiftprune_score_select.restype = i32
+    L.swiftprune_nm_select.argtypes = [vp, i64, i64, i64, i32, vp, i32, i32, vp, vp, u32, vp]
+    L.swiftprune_nm_select.restype = i32
+    L.swiftprune_apply.argtypes = [vp, i64, i64, i64, i32, vp, vp]
+    L.swiftprune_apply.restype = i32
+    L.swiftprune_la_for_sparsity.argtypes = [f, C.POINTER(C.c_float)]
+    L.swiftprune_la_for_sparsity.restype = i32
+    L.swiftprune_stats_workspace_bytes.argtypes = [i64, i64]
+    L.swiftprune_stats_workspace_bytes.restype = C.c_size_t
+    L.swiftprune_strerror.argtypes = [i32]
+    L.swiftprune_strerror.restype = C.c_char_p
+    L.swiftprune_version.argtypes = []
+    L.swiftprune_version.restype = C.c_char_p
+    if path is None:
+        _lib = L
+    return L
+
+
+# ------------------------------------------------------------------ marshalling helpers
+def _dtype_code(t) -> int:
+    import torch
+    if t.dtype == torch.bfloat16:
+        return SP_BF16
+    if t.dtype == torch.float32:
+        return SP_F32
+    raise TypeError(f"tensor must be bfloat16 or float32, got {t.dtype}")
+
+
+def _matrix(t):
+    """(pointer, rows, cols, pitch in elements, dtype code) of a 2-D device tensor with unit column stride."""
+    if t.dim() != 2 or t.stride(1) != 1:
+        raise ValueError("expected a 2-D tensor with unit column stride")
+    if not t.is_cuda:
+        raise ValueError("tensor must live on the GPU (there is no CPU path)")
+    return t.data_ptr(), t.shape[0], t.shape[1], t.stride(0), _dtype_code(t)
+
+
+def _vec(t, dtype, n, name):
+    if t is None:
+        return None
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous() or t.numel() < n:
+        raise ValueError(f"{name}: expected a contiguous {dtype} GPU tensor with at least {n} elements")
+    return t.data_ptr()
+
+
+def _stream(stream):
+    import torch
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return getattr(stream, "cuda_stream", stream)
+
+
+def _check(code: int, where: str):
+    if code != SP_OK:
+        raise SwiftPruneError(code, where)
+
+
+# ------------------------------------------------------------------ host helpers
+def swiftprune_version() -> str:
+    return load_library().swiftprune_version().decode()
+
+
+def swiftprune_strerror(code: int) -> str:
+    return load_library().swiftprune_strerror(int(code)).decode()
+
+
+def swiftprune_la_for_sparsity(sparsity: float) -> float:
+    la = C.c_float()
+    _check(load_library().swiftprune_la_for_sparsity(float(sparsity), C.byref(la)),
+           "swiftprune_la_for_sparsity")
+    return la.value
+
+
+def swiftprune_stats_workspace_bytes(tokens: int, n_in: int) -> int:
+    return int(load_library().swiftprune_stats_workspace_bytes(int(tokens), int(n_in)))
+
+
+# ------------------------------------------------------------------ entry points
+def swiftprune_layer_stats(X, xsq, S, hr, accumulate: bool = False, finalize: bool = True,
+                           workspace=None, stream=None):
+    """X[tokens, in] -> xsq[in], S[1], hr[in] (all fp32 GPU tensors, written in place)."""
+    import torch
+    ptr, tokens, n_in, ldx, dt = _matrix(X)
+    need = swiftprune_stats_workspace_bytes(tokens, n_in)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
+    code = load_library().swiftprune_layer_stats(
+        ptr, tokens, n_in, ldx, dt, _vec(xsq, torch.float32, n_in, "xsq"),
+        _vec(S, torch.float32, 1, "S"), _vec(hr, torch.float32, n_in, "hr"),
+        int(bool(accumulate)), int(bool(finalize)), workspace.data_ptr(),
+        workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(code, "swiftprune_layer_stats")
+    return workspace
+
+
+def swiftprune_score_select(W, hr, keep_mask, sparsity: float = 0.5, alpha: float = 0.125,
+                            beta: float = 0.125, la: float | None = None, row_pruned=None,
+                            scores=None, flags: int = 0, stream=None):
+    """EWMA selection of W[out, in]; keep_mask is int32/uint32 [out, ceil(in/32)]."""
+    import torch
+    ptr, out, n_in, ldw, dt = _matrix(W)
+    words = (n_in + 31) // 32
+    params = sp_ewma_params(float(alpha), float(beta), float("nan") if la is None else float(la))
+    code = load_library().swiftprune_score_select(
+        ptr, out, n_in, ldw, dt, _vec(hr, torch.float32, n_in, "hr"), float(sparsity),
+        C.byref(params), _vec(keep_mask, torch.int32, out * words, "keep_mask"),
+        _vec(row_pruned, torch.int32, out, "row_pruned"),
+        _vec(scores, torch.float32, out * n_in, "scores"), int(flags), _stream(stream))
+    _check(code, "swiftprune_score_select")
+
+
+def swiftprune_nm_select(W, hr, n_keep: int, m_group: int, keep_mask, scores=None, flags: int = 0,
+                         stream=None):
+    import torch
+    ptr, out, n_in, ldw, dt = _matrix(W)
+    words = (n_in + 31) // 32
+    code = load_library().swiftprune_nm_select(
+        ptr, out, n_in, ldw, dt, _vec(hr, torch.float32, n_in, "hr"), int(n_keep), int(m_group),
+        _vec(keep_mask, torch.int32, out * words, "keep_mask"),
+        _vec(scores, torch.float32, out * n_in, "scores"), int(flags), _stream(stream))
+    _check(code, "swiftprune_nm_select")
+
+
+def swiftprune_apply(W, keep_mask, stream=None):
+    import torch
+    ptr, out, n_in, ldw, dt = _matrix(W)
+    words = (n_in + 31) // 32
+    code = load_library().swiftprune_apply(ptr, out, n_in, ldw, dt,
+                                           _vec(keep_mask, torch.int32, out * words, "keep_mask"),
+                                           _stream(stream))
+    _check(code, "swiftprune_apply")
+
+
+# ------------------------------------------------------------------ convenience: one layer
+class LayerBuffers:
+    """Device buffers one layer's calls need (allocated once, reused across layers of the same size)."""
+
+    def __init__(self, out: int, n_in: int, tokens: int, device="cuda"):
+        import torch
+        self.xsq = torch.empty(n_in, dtype=torch.float32, device=device)
+        self.S = torch.empty(1, dtype=torch.float32, device=device)
+        self.hr = torch.empty(n_in, dtype=torch.float32, device=device)
+        self.keep_mask = torch.empty((out, (n_in + 31) // 32), dtype=torch.int32, device=device)
+        self.row_pruned = torch.empty(out, dtype=torch.int32, device=device)
+        self.workspace = torch.empty(swiftprune_stats_workspace_bytes(tokens, n_in), dtype=torch.uint8,
+                                     device=device)
+
+
+def prune_layer(W, X, buffers: LayerBuffers | None = None, sparsity: float = 0.5, nm=None,
+                alpha: float = 0.125, beta: float = 0.125, la: float | None = None, stream=None):
+    """The whole path for one layer, in place on W: statistics, score + selection, apply (fused).
+
+    nm = (n_keep, m_group) selects the structured variant.  Returns the buffers (mask, counts)."""
+    b = buffers or LayerBuffers(W.shape[0], W.shape[1], X.shape[0], W.device)
+    swiftprune_layer_stats(X, b.xsq, b.S, b.hr, workspace=b.workspace, stream=stream)
+    if nm is None:
+        swiftprune_score_select(W, b.hr, b.keep_mask, sparsity=sparsity, alpha=alpha, beta=beta, la=la,
+                                row_pruned=b.row_pruned, flags=SP_APPLY_INPLACE, stream=stream)
+    else:
+        swiftprune_nm_select(W, b.hr, nm[0], nm[1], b.keep_mask, flags=SP_APPLY_INPLACE, stream=stream)
+    return b

@@ -1,0 +1,149 @@
+// C ABI of the SwiftPrune layer path (see include/swiftprune.h): argument
+// checks, path selection (16-byte vector loads vs element-wise) and launches.
+#include "../../include/swiftprune.h"
+
+#include "kernels.hpp"
+
+#include <math.h>
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline int64_t elem_size(int dt) { return dt == SP_BF16 ? 2 : 4; }
+inline bool dtype_ok(int dt) { return dt == SP_F32 || dt == SP_BF16; }
+
+// the 16-byte-vector path of the statistics kernel
+inline bool stats_vec_ok(const void* X, int64_t in, int64_t ldx, int dt) {
+    const int64_t epu = 16 / elem_size(dt);
+    return aligned16(X) && in % epu == 0 && ldx % epu == 0;
+}
+
+// the 16-byte-vector path of the per-weight kernels (8 columns per lane)
+inline bool weight_vec_ok(const void* W, int64_t in, int64_t ldw, int dt, const float* hr,
+                          const float* scores) {
+    const int64_t epu = 16 / elem_size(dt);
+    return aligned16(W) && in % 8 == 0 && ldw % epu == 0 && (hr == nullptr || aligned16(hr)) &&
+           (scores == nullptr || aligned16(scores));
+}
+
+const float kTableRatio[5] = {0.5f, 0.6f, 0.7f, 0.8f, 0.9f};
+const float kTableLa[5] = {0.5f, 0.2f, -0.2f, -0.9f, -1.5f};
+
+}  // namespace
+
+extern "C" {
+
+const char* swiftprune_version(void) { return "0.1.0"; }
+
+const char* swiftprune_strerror(int code) {
+    switch (code) {
+        case SP_OK: return "success";
+        case SP_EINVAL: return "invalid argument";
+        case SP_ENOSPC: return "workspace too small";
+        case SP_EHIP: return "HIP runtime error (see hipGetLastError)";
+        default: return "unknown status";
+    }
+}
+
+int swiftprune_la_for_sparsity(float sparsity, float* la) {
+    if (la == nullptr || !(sparsity >= 0.5f && sparsity <= 0.9f)) return SP_EINVAL;
+    for (int i = 0; i < 5; ++i) {
+        if (fabsf(sparsity - kTableRatio[i]) < 1e-6f) {
+            *la = kTableLa[i];
+            return SP_OK;
+        }
+    }
+    for (int i = 0; i < 4; ++i) {
+        if (sparsity > kTableRatio[i] && sparsity < kTableRatio[i + 1]) {
+            const float t = (sparsity - kTableRatio[i]) / (kTableRatio[i + 1] - kTableRatio[i]);
+            *la = kTableLa[i] + t * (kTableLa[i + 1] - kTableLa[i]);
+            return SP_OK;
+        }
+    }
+    return SP_EINVAL;
+}
+
+size_t swiftprune_stats_workspace_bytes(int64_t tokens, int64_t in) {
+    if (tokens <= 0 || in <= 0) return 0;
+    size_t floats = 0;
+    for (int dt = 0; dt < 2; ++dt)
+        for (int vec = 0; vec < 2; ++vec) {
+            const sp::StatsPlan p = sp::make_stats_plan(tokens, in, dt, vec != 0);
+            if (p.partial_floats > floats) floats = p.partial_floats;
+        }
+    return sp::kStatsHeaderBytes + floats * sizeof(float);
+}
+
+int swiftprune_layer_stats(const void* X, int64_t tokens, int64_t in, int64_t ldx, sp_dtype dt,
+                           float* xsq, float* S, float* hr, int accumulate, int finalize,
+                           void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (X == nullptr || xsq == nullptr || workspace == nullptr) return SP_EINVAL;
+    if (tokens <= 0 || in <= 0 || ldx < in || !dtype_ok((int)dt)) return SP_EINVAL;
+    if (finalize && (S == nullptr || hr == nullptr)) return SP_EINVAL;
+    if (reinterpret_cast<uintptr_t>(X) % elem_size((int)dt) != 0) return SP_EINVAL;
+    if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return SP_EINVAL;
+    if (workspace_bytes < swiftprune_stats_workspace_bytes(tokens, in)) return SP_ENOSPC;
+    const bool vec = stats_vec_ok(X, in, ldx, (int)dt);
+    const hipError_t e = sp::launch_layer_stats(X, tokens, in, ldx, (int)dt, vec, xsq, S, hr, accumulate,
+                                                finalize, workspace, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? SP_OK : SP_EHIP;
+}
+
+int swiftprune_score_select(const void* W, int64_t out, int64_t in, int64_t ldw, sp_dtype dt,
+                            const float* hr, float sparsity, const sp_ewma_params* params,
+                            uint32_t* keep_mask, int32_t* row_pruned, float* scores,
+                            uint32_t flags, void* hip_stream) {
+    if (W == nullptr || hr == nullptr || keep_mask == nullptr) return SP_EINVAL;
+    if (out <= 0 || in <= 0 || ldw < in || !dtype_ok((int)dt)) return SP_EINVAL;
+    if (flags & ~(SP_SEQUENTIAL_ORDER | SP_APPLY_INPLACE)) return SP_EINVAL;
+    if (reinterpret_cast<uintptr_t>(W) % elem_size((int)dt) != 0) return SP_EINVAL;
+    sp_ewma_params p = {0.125f, 0.125f, NAN};
+    if (params != nullptr) p = *params;
+    if (isnan(p.la)) {
+        if (swiftprune_la_for_sparsity(sparsity, &p.la) != SP_OK) return SP_EINVAL;
+    }
+    if (!(p.alpha > 0.0f && p.alpha <= 1.0f) || !(p.beta > 0.0f && p.beta <= 1.0f) || isinf(p.la))
+        return SP_EINVAL;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const bool apply = (flags & SP_APPLY_INPLACE) != 0;
+    hipError_t e;
+    if (flags & SP_SEQUENTIAL_ORDER) {
+        e = sp::launch_ewma_sequential(W, out, in, ldw, (int)dt, hr, p.alpha, p.beta, p.la, keep_mask,
+                                       row_pruned, scores, apply, stream);
+    } else {
+        const bool vec = weight_vec_ok(W, in, ldw, (int)dt, hr, scores);
+        const sp::EwmaConsts c = sp::make_ewma_consts(p.alpha, p.beta, p.la);
+        e = sp::launch_ewma_scan(W, out, in, ldw, (int)dt, vec, hr, c, keep_mask, row_pruned, scores,
+                                 apply, stream);
+    }
+    return e == hipSuccess ? SP_OK : SP_EHIP;
+}
+
+int swiftprune_nm_select(const void* W, int64_t out, int64_t in, int64_t ldw, sp_dtype dt,
+                         const float* hr, int n_keep, int m_group, uint32_t* keep_mask, float* scores,
+                         uint32_t flags, void* hip_stream) {
+    if (W == nullptr || hr == nullptr || keep_mask == nullptr) return SP_EINVAL;
+    if (out <= 0 || in <= 0 || ldw < in || !dtype_ok((int)dt)) return SP_EINVAL;
+    if (m_group != 4 && m_group != 8 && m_group != 16) return SP_EINVAL;
+    if (n_keep <= 0 || n_keep >= m_group || in % m_group != 0) return SP_EINVAL;
+    if (flags & ~SP_APPLY_INPLACE) return SP_EINVAL;
+    if (reinterpret_cast<uintptr_t>(W) % elem_size((int)dt) != 0) return SP_EINVAL;
+    const bool vec = weight_vec_ok(W, in, ldw, (int)dt, hr, scores);
+    const hipError_t e =
+        sp::launch_nm_select(W, out, in, ldw, (int)dt, vec, hr, n_keep, m_group, keep_mask, scores,
+                             (flags & SP_APPLY_INPLACE) != 0, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? SP_OK : SP_EHIP;
+}
+
+int swiftprune_apply(void* W, int64_t out, int64_t in, int64_t ldw, sp_dtype dt,
+                     const uint32_t* keep_mask, void* hip_stream) {
+    if (W == nullptr || keep_mask == nullptr) return SP_EINVAL;
+    if (out <= 0 || in <= 0 || ldw < in || !dtype_ok((int)dt)) return SP_EINVAL;
+    if (reinterpret_cast<uintptr_t>(W) % elem_size((int)dt) != 0) return SP_EINVAL;
+    const bool vec = weight_vec_ok(W, in, ldw, (int)dt, nullptr, nullptr);
+    const hipError_t e = sp::launch_apply(W, out, in, ldw, (int)dt, vec, keep_mask,
+                                          static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? SP_OK : SP_EHIP;
+}
+
+}  // extern "C"

@@ -1,0 +1,163 @@
+// Device helpers shared by the SwiftPrune kernels (gfx950, wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sp {
+
+constexpr int kWave = 64;
+constexpr int kF32 = 0;
+constexpr int kBF16 = 1;
+
+// ---- bf16 <-> fp32 (bf16 is the upper half of an IEEE binary32) ----
+__device__ __forceinline__ float bf16lo(uint32_t pair) { return __uint_as_float(pair << 16); }
+__device__ __forceinline__ float bf16hi(uint32_t pair) { return __uint_as_float(pair & 0xffff0000u); }
+
+// ---- DPP moves; lanes without a valid source (or masked off) receive 0 ----
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ __forceinline__ float dpp_f(float v) {
+    return __int_as_float(
+        __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xf, false));
+}
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, false);
+}
+constexpr int kRowShr1 = 0x111, kRowShr2 = 0x112, kRowShr4 = 0x114, kRowShr8 = 0x118;
+constexpr int kWaveShr1 = 0x138;
+constexpr int kRowBcast15 = 0x142, kRowBcast31 = 0x143;
+constexpr int kQuadSwap1 = 0xB1;  // quad_perm [1,0,3,2]
+constexpr int kQuadSwap2 = 0x4E;  // quad_perm [2,3,0,1]
+
+__device__ __forceinline__ float readlane_f(float v, int lane) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+}
+
+// OR the per-lane bytes of the four lanes of a quad into one word:
+// lane (4k + j) contributes bits [8j, 8j+8).  Every lane of the quad gets the word.
+__device__ __forceinline__ uint32_t quad_gather_bytes(uint32_t byte, int lane) {
+    uint32_t v = byte << (8 * (lane & 3));
+    v |= dpp_u<kQuadSwap1>(v);
+    v |= dpp_u<kQuadSwap2>(v);
+    return v;
+}
+
+// Eight consecutive elements of a row as fp32 plus their raw storage.
+template <int DT>
+struct Chunk8;
+
+template <>
+struct Chunk8<kBF16> {
+    uint32_t raw[4];
+    // 16-byte aligned vector load
+    __device__ __forceinline__ void load_vec(const void* base, int64_t elem_off) {
+        const uint4 v = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(base) + elem_off);
+        raw[0] = v.x; raw[1] = v.y; raw[2] = v.z; raw[3] = v.w;
+    }
+    // element-wise load of the first `valid` elements, the rest read as +0
+    __device__ __forceinline__ void load_elems(const void* base, int64_t elem_off, int valid) {
+        const uint16_t* p = static_cast<const uint16_t*>(base) + elem_off;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint32_t lo = (2 * j < valid) ? p[2 * j] : 0u;
+            uint32_t hi = (2 * j + 1 < valid) ? p[2 * j + 1] : 0u;
+            raw[j] = lo | (hi << 16);
+        }
+    }
+    __device__ __forceinline__ void zero() { raw[0] = raw[1] = raw[2] = raw[3] = 0u; }
+    __device__ __forceinline__ float get(int k) const {
+        return (k & 1) ? bf16hi(raw[k >> 1]) : bf16lo(raw[k >> 1]);
+    }
+    // zero the elements whose keep bit is 0
+    __device__ __forceinline__ void apply(uint32_t keep_byte) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint32_t m = ((keep_byte >> (2 * j)) & 1u ? 0x0000ffffu : 0u) |
+                         ((keep_byte >> (2 * j + 1)) & 1u ? 0xffff0000u : 0u);
+            raw[j] &= m;
+        }
+    }
+    __device__ __forceinline__ void store_vec(void* base, int64_t elem_off) const {
+        *reinterpret_cast<uint4*>(static_cast<uint16_t*>(base) + elem_off) =
+            make_uint4(raw[0], raw[1], raw[2], raw[3]);
+    }
+    __device__ __forceinline__ void store_elems(void* base, int64_t elem_off, int valid) const {
+        uint16_t* p = static_cast<uint16_t*>(base) + elem_off;
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            if (k < valid) p[k] = (uint16_t)((k & 1) ? (raw[k >> 1] >> 16) : (raw[k >> 1] & 0xffffu));
+    }
+};
+
+template <>
+struct Chunk8<kF32> {
+    uint32_t raw[8];
+    __device__ __forceinline__ void load_vec(const void* base, int64_t elem_off) {
+        const uint4* p = reinterpret_cast<const uint4*>(static_cast<const float*>(base) + elem_off);
+        const uint4 a = p[0], b = p[1];
+        raw[0] = a.x; raw[1] = a.y; raw[2] = a.z; raw[3] = a.w;
+        raw[4] = b.x; raw[5] = b.y; raw[6] = b.z; raw[7] = b.w;
+    }
+    __device__ __forceinline__ void load_elems(const void* base, int64_t elem_off, int valid) {
+        const uint32_t* p = static_cast<const uint32_t*>(base) + elem_off;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) raw[k] = (k < valid) ? p[k] : 0u;
+    }
+    __device__ __forceinline__ void zero() {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) raw[k] = 0u;
+    }
+    __device__ __forceinline__ float get(int k) const { return __uint_as_float(raw[k]); }
+    __device__ __forceinline__ void apply(uint32_t keep_byte) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            if (!((keep_byte >> k) & 1u)) raw[k] = 0u;
+    }
+    __device__ __forceinline__ void store_vec(void* base, int64_t elem_off) const {
+        uint4* p = reinterpret_cast<uint4*>(static_cast<float*>(base) + elem_off);
+        p[0] = make_uint4(raw[0], raw[1], raw[2], raw[3]);
+        p[1] = make_uint4(raw[4], raw[5], raw[6], raw[7]);
+    }
+    __device__ __forceinline__ void store_elems(void* base, int64_t elem_off, int valid) const {
+        uint32_t* p = static_cast<uint32_t*>(base) + elem_off;
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            if (k < valid) p[k] = raw[k];
+    }
+};
+
+// Eight consecutive per-channel factors.
+struct Factor8 {
+    float v[8];
+    __device__ __forceinline__ void load_vec(const float* hr, int64_t q) {
+        const float4 a = *reinterpret_cast<const float4*>(hr + q);
+        const float4 b = *reinterpret_cast<const float4*>(hr + q + 4);
+        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+        v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    }
+    __device__ __forceinline__ void load_elems(const float* hr, int64_t q, int valid) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k] = (k < valid) ? hr[q + k] : 0.0f;
+    }
+};
+
+// Contribution score of a weight: (w*w) rounded, times the channel factor, rounded.
+// Written as two separate multiplications so that no contraction can change it.
+__device__ __forceinline__ float score_of(float w, float factor) {
+    const float w2 = __fmul_rn(w, w);
+    return __fmul_rn(w2, factor);
+}
+
+__device__ __forceinline__ void store8(float* dst, const float* v, bool vec, int valid) {
+    if (vec) {
+        reinterpret_cast<float4*>(dst)[0] = make_float4(v[0], v[1], v[2], v[3]);
+        reinterpret_cast<float4*>(dst)[1] = make_float4(v[4], v[5], v[6], v[7]);
+    } else {
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            if (k < valid) dst[k] = v[k];
+    }
+}
+
+}  // namespace sp

@@ -1,0 +1,53 @@
+// Host-side launchers of the SwiftPrune kernels (internal to the library).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace sp {
+
+// ---- step 1: calibration statistics ----
+// Launch geometry of the statistics pass, a pure function of the shape so the
+// workspace size can be computed without a device.
+struct StatsPlan {
+    int epu;                 // elements per 16-byte unit a lane loads (8 bf16 / 4 fp32), 1 = element-wise path
+    int64_t units;           // ceil(in / epu)
+    int nstrips;             // column strips of 64 units (one wavefront wide)
+    int splits;              // token-range splits per strip
+    int64_t rows_per_split;  // tokens handled by one workgroup
+    size_t partial_floats;   // nstrips * splits * 64 * epu
+};
+constexpr size_t kStatsHeaderBytes = 256;  // counters at the start of the workspace
+StatsPlan make_stats_plan(int64_t tokens, int64_t in, int dt, bool vec);
+
+hipError_t launch_layer_stats(const void* X, int64_t tokens, int64_t in, int64_t ldx, int dt, bool vec,
+                              float* xsq, float* S, float* hr, int accumulate, int finalize,
+                              void* workspace, hipStream_t stream);
+
+// ---- steps 2+3: EWMA selection ----
+struct EwmaConsts {
+    float alpha, beta, la;
+    float A_pow[9];     // (1-alpha)^k, k = 0..8
+    float B_pow[9];     // (1-beta)^k
+    double A8_sq[7];    // ((1-alpha)^8)^(2^i), i = 0..6
+    double B8_sq[7];
+};
+EwmaConsts make_ewma_consts(float alpha, float beta, float la);
+
+hipError_t launch_ewma_scan(const void* W, int64_t out, int64_t in, int64_t ldw, int dt, bool vec,
+                            const float* hr, const EwmaConsts& c, uint32_t* keep_mask,
+                            int32_t* row_pruned, float* scores, bool apply, hipStream_t stream);
+hipError_t launch_ewma_sequential(const void* W, int64_t out, int64_t in, int64_t ldw, int dt,
+                                  const float* hr, float alpha, float beta, float la,
+                                  uint32_t* keep_mask, int32_t* row_pruned, float* scores, bool apply,
+                                  hipStream_t stream);
+
+// ---- steps 2+3 structured, step 4 ----
+hipError_t launch_nm_select(const void* W, int64_t out, int64_t in, int64_t ldw, int dt, bool vec,
+                            const float* hr, int n_keep, int m_group, uint32_t* keep_mask,
+                            float* scores, bool apply, hipStream_t stream);
+hipError_t launch_apply(void* W, int64_t out, int64_t in, int64_t ldw, int dt, bool vec,
+                        const uint32_t* keep_mask, hipStream_t stream);
+
+}  // namespace sp

@@ -1,0 +1,332 @@
+"""GPU parity: every entry point of the C-ABI library against the CPU oracle, element by element,
+on the same seeded inputs.
+
+Bars:
+  * masks from the strict-order EWMA kernel and from N:M selection, scores, apply: bit-exact when
+    both sides are given the same channel factor;
+  * statistics (xsq, S, hr): 1e-5 relative (fp32 partial sums on the GPU, fp64 in the oracle);
+  * masks from the scan kernel (or from GPU statistics): a bit may differ only where the oracle's
+    score is within 1e-5 relative of the oracle's threshold for that element (gpu_util.TOL).
+"""
+import sys
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+A, B = 0.125, 0.125
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2501_16376_amd import binding
+    binding.load_library()
+    return torch.device("cuda:0")
+
+
+def _stats_gpu(X_dev, n, accumulate_chunks=None):
+    import torch
+    from paper_2501_16376_amd import binding as b
+    xsq = torch.empty(n, dtype=torch.float32, device=X_dev.device)
+    S = torch.empty(1, dtype=torch.float32, device=X_dev.device)
+    hr = torch.empty(n, dtype=torch.float32, device=X_dev.device)
+    if accumulate_chunks is None:
+        b.swiftprune_layer_stats(X_dev, xsq, S, hr)
+    else:
+        bounds = accumulate_chunks
+        for i in range(len(bounds) - 1):
+            b.swiftprune_layer_stats(X_dev[bounds[i]:bounds[i + 1]], xsq, S, hr, accumulate=(i > 0),
+                                     finalize=(i == len(bounds) - 2))
+    torch.cuda.synchronize()
+    return xsq.cpu().numpy(), float(S.cpu().numpy()[0]), hr.cpu().numpy()
+
+
+def _select_gpu(W_dev, hr_dev, la, flags=0, want_scores=False, alpha=A, beta=B):
+    import torch
+    from paper_2501_16376_amd import binding as b
+    from gpu_util import mask_to_host
+    out, n = W_dev.shape
+    mask = torch.full((out, (n + 31) // 32), -1, dtype=torch.int32, device=W_dev.device)
+    cnt = torch.full((out,), -7, dtype=torch.int32, device=W_dev.device)
+    sc = torch.empty((out, n), dtype=torch.float32, device=W_dev.device) if want_scores else None
+    b.swiftprune_score_select(W_dev, hr_dev, mask, alpha=alpha, beta=beta, la=la, row_pruned=cnt,
+                              scores=sc, flags=flags)
+    torch.cuda.synchronize()
+    return mask_to_host(mask), cnt.cpu().numpy(), (None if sc is None else sc.cpu().numpy())
+
+
+def _nm_gpu(W_dev, hr_dev, nk, m, flags=0, want_scores=False):
+    import torch
+    from paper_2501_16376_amd import binding as b
+    from gpu_util import mask_to_host
+    out, n = W_dev.shape
+    mask = torch.full((out, (n + 31) // 32), -1, dtype=torch.int32, device=W_dev.device)
+    sc = torch.empty((out, n), dtype=torch.float32, device=W_dev.device) if want_scores else None
+    b.swiftprune_nm_select(W_dev, hr_dev, nk, m, mask, scores=sc, flags=flags)
+    torch.cuda.synchronize()
+    return mask_to_host(mask), (None if sc is None else sc.cpu().numpy())
+
+
+def _layer_case(orc, gpu, out, n, tokens, dtype, seed, las=(0.5,), nms=((2, 4), (4, 8)), pitch_pad=0,
+                n_outlier=None):
+    """Full parity of one layer shape; returns the number of tolerated scan-vs-oracle differences."""
+    import torch
+    from paper_2501_16376_amd import binding as b, synth
+    from gpu_util import to_device, check_ewma_mask, mask_to_host
+    say(f"[case] out={out} in={n} tokens={tokens} dtype={dtype} seed={seed} pad={pitch_pad}")
+    Wh, Xh = synth.layer_inputs(out, n, tokens, seed=seed, dtype=dtype, n_outlier=n_outlier)
+    if pitch_pad:
+        Wp = np.zeros((out, n + pitch_pad), dtype=Wh.dtype)
+        Wp[:, :n] = Wh
+        Xp = np.full((tokens, n + pitch_pad), 0x4000 if dtype == "bf16" else 2.0, dtype=Xh.dtype)
+        Xp[:, :n] = Xh
+        W_dev = to_device(Wp, gpu)[:, :n]
+        X_dev = to_device(Xp, gpu)[:, :n]
+    else:
+        W_dev, X_dev = to_device(Wh, gpu), to_device(Xh, gpu)
+
+    # --- step 1
+    xsq_o, S_o, hr_o = orc.layer_stats(Xh)
+    xsq_g, S_g, hr_g = _stats_gpu(X_dev, n)
+    assert np.allclose(xsq_g, xsq_o, rtol=1e-5, atol=0), np.abs(xsq_g / xsq_o - 1).max()
+    assert abs(S_g - S_o) <= 1e-5 * abs(S_o)
+    assert np.allclose(hr_g, hr_o, rtol=1e-5, atol=0)
+    hr_dev = to_device(hr_o, gpu)
+
+    tolerated = 0
+    for la in las:
+        # --- strict order, same factor: bit-exact masks, counts and scores
+        mask_o, cnt_o, sc_o = orc.ewma_select(Wh, hr_o, A, B, la, want_scores=True)
+        m_seq, c_seq, sc_seq = _select_gpu(W_dev, hr_dev, la, flags=b.SP_SEQUENTIAL_ORDER, want_scores=True)
+        assert np.array_equal(m_seq, mask_o), f"strict-order mask differs, la={la}"
+        assert np.array_equal(c_seq, cnt_o)
+        assert np.array_equal(sc_seq.view(np.uint32), sc_o.view(np.uint32))
+        # --- scan path, same factor: rounding-level differences only
+        m_scan, c_scan, sc_scan = _select_gpu(W_dev, hr_dev, la, want_scores=True)
+        assert np.array_equal(sc_scan.view(np.uint32), sc_o.view(np.uint32))
+        tolerated += check_ewma_mask(orc, Wh, hr_o, A, B, la, m_scan, c_scan)
+        # --- scan path on the GPU's own statistics (end to end)
+        m_e2e, c_e2e, sc_e2e = _select_gpu(W_dev, to_device(hr_g, gpu), la, want_scores=True)
+        assert np.allclose(sc_e2e, sc_o, rtol=1e-5, atol=0)
+        tolerated += check_ewma_mask(orc, Wh, hr_o, A, B, la, m_e2e, c_e2e)
+
+    # --- N:M: bit-exact with the same factor
+    for nk, m in nms:
+        if n % m:
+            continue
+        nm_o, nsc_o = orc.nm_select(Wh, hr_o, nk, m, want_scores=True)
+        nm_g, nsc_g = _nm_gpu(W_dev, hr_dev, nk, m, want_scores=True)
+        assert np.array_equal(nm_g, nm_o), f"{nk}:{m} mask differs"
+        assert np.array_equal(nsc_g.view(np.uint32), nsc_o.view(np.uint32))
+
+    # --- apply, separate and fused
+    mask_o, _, _ = orc.ewma_select(Wh, hr_o, A, B, las[0])
+    ref = orc.apply(Wh.copy(), mask_o)
+    W1 = W_dev.clone() if not pitch_pad else to_device(Wp, gpu)[:, :n]
+    b.swiftprune_apply(W1, to_device(mask_o.view(np.int32), gpu))
+    torch.cuda.synchronize()
+    assert np.array_equal(synth.torch_to_host_bits(W1), ref)
+    W2 = W_dev.clone() if not pitch_pad else to_device(Wp, gpu)[:, :n]
+    mk = torch.empty((out, (n + 31) // 32), dtype=torch.int32, device=gpu)
+    b.swiftprune_score_select(W2, hr_dev, mk, la=las[0], flags=b.SP_APPLY_INPLACE | b.SP_SEQUENTIAL_ORDER)
+    torch.cuda.synchronize()
+    assert np.array_equal(synth.torch_to_host_bits(W2), ref)
+    W3 = W_dev.clone() if not pitch_pad else to_device(Wp, gpu)[:, :n]
+    b.swiftprune_score_select(W3, hr_dev, mk, la=las[0], flags=b.SP_APPLY_INPLACE)
+    torch.cuda.synchronize()
+    ref3 = orc.apply(Wh.copy(), mask_to_host(mk))
+    assert np.array_equal(synth.torch_to_host_bits(W3), ref3)      # fused apply agrees with its own mask
+    if n % 4 == 0:
+        nm_o, _ = orc.nm_select(Wh, hr_o, 2, 4)
+        W4 = W_dev.clone() if not pitch_pad else to_device(Wp, gpu)[:, :n]
+        b.swiftprune_nm_select(W4, hr_dev, 2, 4, mk, flags=b.SP_APPLY_INPLACE)
+        torch.cuda.synchronize()
+        assert np.array_equal(synth.torch_to_host_bits(W4), orc.apply(Wh.copy(), nm_o))
+    if pitch_pad:                                                     # padding columns untouched
+        for Wt in (W1, W2, W3):
+            full = synth.torch_to_host_bits(Wt._base if Wt._base is not None else Wt)
+            assert np.all(full[:, n:] == 0)
+    return tolerated
+
+
+def test_config1_fp32(orc, gpu):
+    """The small case: W 256x256 fp32, X 128x256 fp32, 4 outlier channels, every la of the paper's table."""
+    t = _layer_case(orc, gpu, 256, 256, 128, "f32", seed=0, las=(0.5, 0.2, -0.2, -0.9, -1.5),
+                    nms=((2, 4), (4, 8), (1, 4), (3, 4), (8, 16)), n_outlier=4)
+    say(f"config 1: {t} tolerated scan differences")
+
+
+@pytest.mark.parametrize("out,n,tokens,dtype,pad", [
+    (300, 1376, 5000, "bf16", 0),      # several 512-column segments + ragged tail; rows not a multiple of 4/8
+    (70, 2056, 1111, "bf16", 0),       # in % 8 == 0 but not % 32
+    (33, 1001, 777, "bf16", 0),        # odd width: element-wise path
+    (65, 1000, 300, "bf16", 24),       # row pitch > columns (strided view), vector path
+    (19, 999, 300, "f32", 5),          # fp32, odd width and odd pitch
+    (129, 520, 2100, "f32", 0),        # fp32 vector path
+    (5, 8, 3, "bf16", 0),              # one chunk
+    (3, 1, 1, "f32", 0),               # a single column, a single token
+    (1, 4096, 64, "bf16", 0),          # a single row
+])
+def test_shapes(orc, gpu, out, n, tokens, dtype, pad):
+    t = _layer_case(orc, gpu, out, n, tokens, dtype, seed=out + n, pitch_pad=pad,
+                    nms=((2, 4), (4, 8), (1, 4), (6, 8), (4, 16)))
+    say(f"  tolerated scan differences: {t}")
+
+
+def test_other_alpha_beta(orc, gpu):
+    """alpha != beta, large and small decay, negative and large la."""
+    from paper_2501_16376_amd import binding as b, synth
+    from gpu_util import to_device, check_ewma_mask
+    Wh, Xh = synth.layer_inputs(64, 1536, 256, seed=77, dtype="bf16")
+    _, _, hr_o = orc.layer_stats(Xh)
+    W_dev, hr_dev = to_device(Wh, gpu), to_device(hr_o, gpu)
+    for alpha, beta, la in [(0.3, 0.07, -0.9), (0.02, 0.5, 0.4), (1.0, 1.0, 0.1), (0.9, 0.01, 2.0),
+                            (0.125, 0.25, 4.0), (0.001, 0.001, 0.0)]:
+        say(f"[case] alpha={alpha} beta={beta} la={la}")
+        mask_o, cnt_o, _ = orc.ewma_select(Wh, hr_o, alpha, beta, la)
+        m_seq, c_seq, _ = _select_gpu(W_dev, hr_dev, la, flags=b.SP_SEQUENTIAL_ORDER, alpha=alpha, beta=beta)
+        assert np.array_equal(m_seq, mask_o) and np.array_equal(c_seq, cnt_o)
+        m_scan, c_scan, _ = _select_gpu(W_dev, hr_dev, la, alpha=alpha, beta=beta)
+        check_ewma_mask(orc, Wh, hr_o, alpha, beta, la, m_scan, c_scan)
+
+
+def test_la_from_sparsity(orc, gpu):
+    """la = NaN -> looked up from the sparsity argument (paper's table)."""
+    import torch
+    from paper_2501_16376_amd import binding as b, synth
+    from gpu_util import to_device, mask_to_host
+    Wh, Xh = synth.layer_inputs(32, 512, 128, seed=5, dtype="bf16")
+    _, _, hr_o = orc.layer_stats(Xh)
+    W_dev, hr_dev = to_device(Wh, gpu), to_device(hr_o, gpu)
+    mask = torch.empty((32, 16), dtype=torch.int32, device=gpu)
+    b.swiftprune_score_select(W_dev, hr_dev, mask, sparsity=0.7, la=None, flags=b.SP_SEQUENTIAL_ORDER)
+    torch.cuda.synchronize()
+    mask_o, _, _ = orc.ewma_select(Wh, hr_o, A, B, -0.2)
+    assert np.array_equal(mask_to_host(mask), mask_o)
+
+
+def test_stats_chunked_and_deterministic(orc, gpu):
+    """Token chunks accumulate to the one-shot result; repeated runs are bit-identical."""
+    from paper_2501_16376_amd import synth
+    from gpu_util import to_device
+    Wh, Xh = synth.layer_inputs(1, 2048, 9000, seed=9, dtype="bf16")
+    X_dev = to_device(Xh, gpu)
+    xsq_o, S_o, hr_o = orc.layer_stats(Xh)
+    one = _stats_gpu(X_dev, 2048)
+    two = _stats_gpu(X_dev, 2048)
+    assert np.array_equal(one[0], two[0]) and one[1] == two[1] and np.array_equal(one[2], two[2])
+    chunked = _stats_gpu(X_dev, 2048, accumulate_chunks=[0, 1000, 4097, 9000])
+    assert np.allclose(chunked[0], xsq_o, rtol=1e-5, atol=0)
+    assert abs(chunked[1] - S_o) <= 1e-5 * S_o
+    assert np.allclose(chunked[2], hr_o, rtol=1e-5, atol=0)
+
+
+def test_degenerate_statistics(orc, gpu):
+    """All-zero activations -> S = 0, factor 1/2; one channel holding all the energy -> clamped denominator."""
+    import torch
+    X = torch.zeros((64, 256), dtype=torch.bfloat16, device=gpu)
+    xsq, S, hr = _stats_gpu(X, 256)
+    assert np.all(xsq == 0) and S == 0 and np.all(hr == 0.5)
+    X[:, 7] = 3.0
+    xsq, S, hr = _stats_gpu(X, 256)
+    xsq_o, S_o, hr_o = orc.layer_stats(X.cpu().view(torch.int16).numpy().view(np.uint16))
+    assert np.array_equal(xsq, xsq_o) and S == S_o and np.array_equal(hr, hr_o)
+    assert hr[7] == np.float32(0.5) / np.finfo(np.float32).eps
+
+
+def test_all_ones_exact(orc, gpu):
+    """All-ones input: xsq = T, S = T*in, factor exactly 0.5/(1 - 1/in) - exact in fp32."""
+    import torch
+    X = torch.ones((4096, 1024), dtype=torch.bfloat16, device=gpu)
+    xsq, S, hr = _stats_gpu(X, 1024)
+    assert np.all(xsq == 4096.0) and S == 4096.0 * 1024
+    assert np.all(hr == np.float32(0.5) / (np.float32(1) - np.float32(1 / 1024)))
+
+
+def _full_size_layer(orc, gpu, out, n, seed, sample_cols=None):
+    """A Llama-sized layer at the full 128x2048 calibration tokens, in the launch configuration the
+    benchmark times.  Statistics: against the oracle on all columns (or a column sample for wide
+    layers; S then against the fp64 sum of the GPU's own xsq).  Selection: whole matrix."""
+    import torch
+    from paper_2501_16376_amd import binding as b, synth
+    from gpu_util import to_device, check_ewma_mask
+    tokens = synth.CALIB_TOKENS
+    say(f"[full] out={out} in={n} tokens={tokens}: generating")
+    X = synth.device_activations(tokens, n, seed=seed, device=gpu)
+    W = synth.device_weights(out, n, seed=seed + 1, device=gpu)
+    xsq_g, S_g, hr_g = _stats_gpu(X, n)
+    say("[full] statistics on the oracle")
+    if sample_cols is None:
+        Xh = synth.torch_to_host_bits(X)
+        xsq_o, S_o, hr_o = orc.layer_stats(Xh)
+        del Xh
+        assert np.allclose(xsq_g, xsq_o, rtol=1e-5, atol=0), np.abs(xsq_g / xsq_o - 1).max()
+        assert abs(S_g - S_o) <= 1e-5 * S_o
+        assert np.allclose(hr_g, hr_o, rtol=1e-5, atol=0)
+        say(f"[full] xsq max rel err {np.abs(xsq_g / xsq_o - 1).max():.2e}")
+    else:
+        rng = np.random.default_rng(seed)
+        cols = np.unique(np.concatenate([rng.choice(n, sample_cols, replace=False),
+                                         np.argsort(xsq_g)[-16:], [0, n - 1]]))
+        Xs = synth.torch_to_host_bits(X[:, torch.from_numpy(cols).to(gpu)])
+        acc = orc.stats_accumulate(Xs)
+        assert np.allclose(xsq_g[cols], acc, rtol=1e-5, atol=0), np.abs(xsq_g[cols] / acc - 1).max()
+        S64 = float(np.sum(xsq_g.astype(np.float64)))
+        assert abs(S_g - S64) <= 1e-6 * S64
+        hr_o = orc.channel_factor_f32(xsq_g, S_g)
+        assert np.array_equal(hr_g, hr_o)
+    del X
+    torch.cuda.empty_cache()
+    Wh = synth.torch_to_host_bits(W)
+    hr_dev = to_device(hr_o, gpu)
+    say("[full] strict-order selection")
+    mask_o, cnt_o, _ = orc.ewma_select(Wh, hr_o, A, B, 0.5)
+    m_seq, c_seq, _ = _select_gpu(W, hr_dev, 0.5, flags=b.SP_SEQUENTIAL_ORDER)
+    assert np.array_equal(m_seq, mask_o) and np.array_equal(c_seq, cnt_o)
+    say("[full] scan selection")
+    m_scan, c_scan, _ = _select_gpu(W, hr_dev, 0.5)
+    t = check_ewma_mask(orc, Wh, hr_o, A, B, 0.5, m_scan, c_scan)
+    say(f"[full] scan vs oracle: {t} tolerated differences of {out * n} weights; "
+        f"sparsity {cnt_o.sum() / (out * n):.4f}")
+    for nk, m in ((2, 4), (4, 8)):
+        nm_o, _ = orc.nm_select(Wh, hr_o, nk, m)
+        nm_g, _ = _nm_gpu(W, hr_dev, nk, m)
+        assert np.array_equal(nm_g, nm_o)
+    # fused select + apply as the benchmark runs it
+    W2 = W.clone()
+    bufs = b.LayerBuffers(out, n, 16, gpu)
+    b.swiftprune_score_select(W2, hr_dev, bufs.keep_mask, la=0.5, row_pruned=bufs.row_pruned,
+                              flags=b.SP_APPLY_INPLACE)
+    torch.cuda.synchronize()
+    from gpu_util import mask_to_host
+    assert np.array_equal(mask_to_host(bufs.keep_mask), m_scan)
+    assert np.array_equal(synth.torch_to_host_bits(W2), orc.apply(Wh.copy(), m_scan))
+
+
+def test_full_size_q_proj(orc, gpu):
+    _full_size_layer(orc, gpu, 4096, 4096, seed=100)
+
+
+def test_full_size_kv_proj_8b(orc, gpu):
+    _full_size_layer(orc, gpu, 1024, 4096, seed=200, sample_cols=192)
+
+
+def test_full_size_gate_8b(orc, gpu):
+    _full_size_layer(orc, gpu, 14336, 4096, seed=300, sample_cols=192)
+
+
+def test_full_size_down_8b(orc, gpu):
+    _full_size_layer(orc, gpu, 4096, 14336, seed=400, sample_cols=192)
+
+
+def test_full_size_down_7b(orc, gpu):
+    _full_size_layer(orc, gpu, 4096, 11008, seed=500, sample_cols=192)
