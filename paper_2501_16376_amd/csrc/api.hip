@@ -65,13 +65,13 @@ int swiftprune_la_for_sparsity(float sparsity, float* la) {
 
 size_t swiftprune_stats_workspace_bytes(int64_t tokens, int64_t in) {
     if (tokens <= 0 || in <= 0) return 0;
-    size_t floats = 0;
+    size_t bytes = 0;
     for (int dt = 0; dt < 2; ++dt)
         for (int vec = 0; vec < 2; ++vec) {
-            const sp::StatsPlan p = sp::make_stats_plan(tokens, in, dt, vec != 0);
-            if (p.partial_floats > floats) floats = p.partial_floats;
+            const size_t b = sp::stats_workspace_bytes(sp::make_stats_plan(tokens, in, dt, vec != 0));
+            if (b > bytes) bytes = b;
         }
-    return sp::kStatsHeaderBytes + floats * sizeof(float);
+    return bytes;
 }
 
 int swiftprune_layer_stats(const void* X, int64_t tokens, int64_t in, int64_t ldx, sp_dtype dt,

@@ -6,6 +6,9 @@
 
 namespace sp {
 
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
 constexpr int kWave = 64;
 constexpr int kF32 = 0;
 constexpr int kBF16 = 1;
@@ -50,9 +53,10 @@ struct Chunk8;
 template <>
 struct Chunk8<kBF16> {
     uint32_t raw[4];
-    // 16-byte aligned vector load
+    // 16-byte aligned vector load; weights are streamed once, so the load is non-temporal
     __device__ __forceinline__ void load_vec(const void* base, int64_t elem_off) {
-        const uint4 v = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(base) + elem_off);
+        const u32x4 v = __builtin_nontemporal_load(
+            reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(base) + elem_off));
         raw[0] = v.x; raw[1] = v.y; raw[2] = v.z; raw[3] = v.w;
     }
     // element-wise load of the first `valid` elements, the rest read as +0
@@ -94,8 +98,8 @@ template <>
 struct Chunk8<kF32> {
     uint32_t raw[8];
     __device__ __forceinline__ void load_vec(const void* base, int64_t elem_off) {
-        const uint4* p = reinterpret_cast<const uint4*>(static_cast<const float*>(base) + elem_off);
-        const uint4 a = p[0], b = p[1];
+        const u32x4* p = reinterpret_cast<const u32x4*>(static_cast<const float*>(base) + elem_off);
+        const u32x4 a = __builtin_nontemporal_load(p), b = __builtin_nontemporal_load(p + 1);
         raw[0] = a.x; raw[1] = a.y; raw[2] = a.z; raw[3] = a.w;
         raw[4] = b.x; raw[5] = b.y; raw[6] = b.z; raw[7] = b.w;
     }

@@ -13,13 +13,16 @@ namespace sp {
 struct StatsPlan {
     int epu;                 // elements per 16-byte unit a lane loads (8 bf16 / 4 fp32), 1 = element-wise path
     int64_t units;           // ceil(in / epu)
-    int nstrips;             // column strips of 64 units (one wavefront wide)
-    int splits;              // token-range splits per strip
+    int strip_units;         // units per column strip (<= 256, one per lane of a workgroup)
+    int nstrips;             // column strips
+    int splits;              // token ranges per strip
     int64_t rows_per_split;  // tokens handled by one workgroup
-    size_t partial_floats;   // nstrips * splits * 64 * epu
+    int combine_groups;      // workgroups of the combine kernel (64 columns each)
+    size_t partial_floats;   // splits * units * epu
 };
 constexpr size_t kStatsHeaderBytes = 256;  // counters at the start of the workspace
 StatsPlan make_stats_plan(int64_t tokens, int64_t in, int dt, bool vec);
+size_t stats_workspace_bytes(const StatsPlan& p);  // header + per-workgroup S sums + partial rows
 
 hipError_t launch_layer_stats(const void* X, int64_t tokens, int64_t in, int64_t ldx, int dt, bool vec,
                               float* xsq, float* S, float* hr, int accumulate, int finalize,
