@@ -66,15 +66,19 @@ typedef struct {
  *   xsq        [in] fp32: accumulate == 0 -> overwritten with sum_t X[t,q]^2;
  *              accumulate != 0 -> that sum is ADDED to the values already there
  *              (so X may arrive in token chunks)              (device, read/write)
- *   S, hr      written only when finalize != 0:  S[0] = sum_q xsq[q],
- *              hr[q] = 0.5 / (1 - xsq[q]/S)  (per-channel factor of the score).
+ *   S          [1] fp32, required: the total sum_q xsq[q]; overwritten when
+ *              accumulate == 0, added to when accumulate != 0 (it must then hold
+ *              what the previous chunk's call left)           (device, read/write)
+ *   hr         [in] fp32, written only when finalize != 0 (may be NULL otherwise):
+ *              hr[q] = 0.5 / (1 - xsq[q]/S), the per-channel factor of the score.
  *              S == 0 gives hr = 0.5; a denominator <= 0 is replaced by FLT_EPSILON.
- *              May be NULL when finalize == 0.                 (device, write)
  *   workspace  >= swiftprune_stats_workspace_bytes(tokens, in) bytes, 256-byte
  *              aligned, contents irrelevant on entry, clobbered (device)
  *
- * Sums run in fp32 over chains of at most a few hundred terms and are then
- * combined in fp64 in a fixed order: the result does not depend on scheduling.
+ * Per-lane sums run in fp32 over chains of at most a quarter of a workgroup's
+ * token range (a few thousand terms) and are then combined in fp64 in a fixed
+ * order: the result does not depend on scheduling.  S is the fp64 sum of the
+ * fp32 partial sums, rounded once.
  * Fast path: X 16-byte aligned, ldx and in multiples of 16 bytes worth of
  * elements; anything else takes an element-wise path with the same result.
  */

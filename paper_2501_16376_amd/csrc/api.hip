@@ -79,7 +79,7 @@ int swiftprune_layer_stats(const void* X, int64_t tokens, int64_t in, int64_t ld
                            void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (X == nullptr || xsq == nullptr || workspace == nullptr) return SP_EINVAL;
     if (tokens <= 0 || in <= 0 || ldx < in || !dtype_ok((int)dt)) return SP_EINVAL;
-    if (finalize && (S == nullptr || hr == nullptr)) return SP_EINVAL;
+    if (S == nullptr || (finalize && hr == nullptr)) return SP_EINVAL;
     if (reinterpret_cast<uintptr_t>(X) % elem_size((int)dt) != 0) return SP_EINVAL;
     if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return SP_EINVAL;
     if (workspace_bytes < swiftprune_stats_workspace_bytes(tokens, in)) return SP_ENOSPC;

@@ -29,6 +29,7 @@
 namespace sp {
 
 constexpr int kScanWaves = 4;  // rows per workgroup (one wavefront each)
+constexpr int kPrefetch = 4;   // row segments (16-byte loads per lane) in flight per wavefront
 
 struct ScanLaneConsts {
     float shift;   // m^lane          : weight of the carried-in state at this lane
@@ -59,7 +60,7 @@ __device__ __forceinline__ ScanLaneConsts make_lane_consts(const double* sq, int
 
 // Inclusive scan R_j = sum_{i <= j} m^(j-i) v_i over the 64 lanes, then the
 // state entering lane j:  R_{j-1} + m^j * carry.
-__device__ __forceinline__ float scan_entering(float v, const ScanLaneConsts& c, float carry, int lane) {
+__device__ __forceinline__ float scan_entering(float v, const ScanLaneConsts& c, float carry) {
     float r = v;
     r = fmaf(c.m1, dpp_f<kRowShr1>(r), r);
     r = fmaf(c.m2, dpp_f<kRowShr2>(r), r);
@@ -67,7 +68,6 @@ __device__ __forceinline__ float scan_entering(float v, const ScanLaneConsts& c,
     r = fmaf(c.m8, dpp_f<kRowShr8>(r), r);
     r = fmaf(c.cross15, dpp_f<kRowBcast15, 0xA>(r), r);
     r = fmaf(c.cross31, dpp_f<kRowBcast31, 0xC>(r), r);
-    (void)lane;
     return fmaf(c.shift, carry, dpp_f<kWaveShr1>(r));
 }
 
@@ -90,83 +90,90 @@ __global__ __launch_bounds__(kScanWaves* kWave) void ewma_scan_kernel(
     float carry_e = 0.f, carry_d = 0.f;
     int pruned = 0;
 
-    Chunk8<DT> cur;
-    {
-        const int64_t q0 = (int64_t)lane * 8;
-        const int valid = (int)min((int64_t)8, max((int64_t)0, in - q0));
-        if (VEC) { if (valid) cur.load_vec(W, row * ldw + q0); else cur.zero(); }
-        else cur.load_elems(W, row * ldw + q0, valid);
-    }
-
-    for (int64_t seg = 0; seg < nseg; ++seg) {
+    // ring of kPrefetch row segments in flight; the factors are fetched one segment ahead
+    auto load_chunk = [&](Chunk8<DT>& ch, int64_t seg) {
         const int64_t q0 = (seg << 9) + (int64_t)lane * 8;
         const int valid = (int)min((int64_t)8, max((int64_t)0, in - q0));
-
-        // prefetch the next segment of the row
-        Chunk8<DT> nxt;
-        nxt.zero();
-        if (seg + 1 < nseg) {
-            const int64_t qn = q0 + 512;
-            const int vn = (int)min((int64_t)8, max((int64_t)0, in - qn));
-            if (VEC) { if (vn) nxt.load_vec(W, row * ldw + qn); }
-            else nxt.load_elems(W, row * ldw + qn, vn);
-        }
-
-        Factor8 f;
+        if (VEC) { if (valid) ch.load_vec(W, row * ldw + q0); else ch.zero(); }
+        else ch.load_elems(W, row * ldw + q0, valid);
+    };
+    auto load_factor = [&](Factor8& f, int64_t seg) {
+        const int64_t q0 = (seg << 9) + (int64_t)lane * 8;
+        const int valid = (int)min((int64_t)8, max((int64_t)0, in - q0));
         if (VEC) { if (valid) f.load_vec(hr, q0); else f.load_elems(hr, q0, 0); }
         else f.load_elems(hr, q0, valid);
+    };
+    Chunk8<DT> ring[kPrefetch];
+#pragma unroll
+    for (int j = 0; j < kPrefetch; ++j) load_chunk(ring[j], j);
+    Factor8 f;
+    load_factor(f, 0);
 
-        float L[8];
+    for (int64_t base = 0; base < nseg; base += kPrefetch) {
 #pragma unroll
-        for (int k = 0; k < 8; ++k) L[k] = score_of(cur.get(k), f.v[k]);
-        if (scores != nullptr && valid) store8(scores + row * in + q0, L, VEC, valid);
+        for (int j = 0; j < kPrefetch; ++j) {
+            const int64_t seg = base + j;
+            if (seg >= nseg) break;  // uniform over the wavefront
+            const int64_t q0 = (seg << 9) + (int64_t)lane * 8;
+            const int valid = (int)min((int64_t)8, max((int64_t)0, in - q0));
 
-        if (seg == 0) carry_e = readlane_f(L[0], 0);  // est starts at the row's first score
+            Chunk8<DT> cur = ring[j];
+            load_chunk(ring[j], seg + kPrefetch);  // reads nothing beyond the row end
+            Factor8 fn;
+            load_factor(fn, seg + 1);
 
-        // 1. lane-local est from a zero state
-        float e[8];
-        e[0] = c.alpha * L[0];
+            float L[8];
 #pragma unroll
-        for (int k = 1; k < 8; ++k) e[k] = fmaf(c.A_pow[1], e[k - 1], c.alpha * L[k]);
-        // 2. est entering this lane
-        const float e_in = scan_entering(e[7], ce, carry_e, lane);
-        // 3. true est, deviations, lane-local dev
-        float d[8];
+            for (int k = 0; k < 8; ++k) L[k] = score_of(cur.get(k), f.v[k]);
+            f = fn;
+            if (scores != nullptr && valid) store8(scores + row * in + q0, L, VEC, valid);
+
+            if (seg == 0) carry_e = readlane_f(L[0], 0);  // est starts at the row's first score
+
+            // 1. lane-local est from a zero state
+            float e[8];
+            e[0] = c.alpha * L[0];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) e[k] = fmaf(c.A_pow[k + 1], e_in, e[k]);
-        d[0] = c.beta * fabsf(e[0] - L[0]);
+            for (int k = 1; k < 8; ++k) e[k] = fmaf(c.A_pow[1], e[k - 1], c.alpha * L[k]);
+            // 2. est entering this lane
+            const float e_in = scan_entering(e[7], ce, carry_e);
+            // 3. true est, deviations, lane-local dev
+            float d[8];
 #pragma unroll
-        for (int k = 1; k < 8; ++k) d[k] = fmaf(c.B_pow[1], d[k - 1], c.beta * fabsf(e[k] - L[k]));
-        const float d_in = scan_entering(d[7], cd, carry_d, lane);
+            for (int k = 0; k < 8; ++k) e[k] = fmaf(c.A_pow[k + 1], e_in, e[k]);
+            d[0] = c.beta * fabsf(e[0] - L[0]);
 #pragma unroll
-        for (int k = 0; k < 8; ++k) d[k] = fmaf(c.B_pow[k + 1], d_in, d[k]);
-        // 4. decisions from the state before each element
-        uint32_t keep = 0u;
-        {
-            const float thr = fmaf(neg_la, d_in, e_in);
-            keep |= (L[0] < thr) ? 0u : 1u;
+            for (int k = 1; k < 8; ++k) d[k] = fmaf(c.B_pow[1], d[k - 1], c.beta * fabsf(e[k] - L[k]));
+            const float d_in = scan_entering(d[7], cd, carry_d);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) d[k] = fmaf(c.B_pow[k + 1], d_in, d[k]);
+            // 4. decisions from the state before each element
+            uint32_t keep = 0u;
+            {
+                const float thr = fmaf(neg_la, d_in, e_in);
+                keep |= (L[0] < thr) ? 0u : 1u;
+            }
+#pragma unroll
+            for (int k = 1; k < 8; ++k) {
+                const float thr = fmaf(neg_la, d[k - 1], e[k - 1]);
+                keep |= (L[k] < thr) ? 0u : (1u << k);
+            }
+            keep &= (valid >= 8) ? 0xffu : ((1u << valid) - 1u);
+            pruned += valid - __popc(keep);
+
+            carry_e = readlane_f(e[7], kWave - 1);
+            carry_d = readlane_f(d[7], kWave - 1);
+
+            const uint32_t word = quad_gather_bytes(keep, lane);
+            const int64_t widx = (seg << 4) + (lane >> 2);
+            if ((lane & 3) == 0 && widx < mask_words) keep_mask[row * mask_words + widx] = word;
+
+            if (apply && valid) {
+                cur.apply(keep);
+                if (VEC) cur.store_vec(W, row * ldw + q0);
+                else cur.store_elems(W, row * ldw + q0, valid);
+            }
         }
-#pragma unroll
-        for (int k = 1; k < 8; ++k) {
-            const float thr = fmaf(neg_la, d[k - 1], e[k - 1]);
-            keep |= (L[k] < thr) ? 0u : (1u << k);
-        }
-        keep &= (valid >= 8) ? 0xffu : ((1u << valid) - 1u);
-        pruned += valid - __popc(keep);
-
-        carry_e = readlane_f(e[7], kWave - 1);
-        carry_d = readlane_f(d[7], kWave - 1);
-
-        const uint32_t word = quad_gather_bytes(keep, lane);
-        const int64_t widx = (seg << 4) + (lane >> 2);
-        if ((lane & 3) == 0 && widx < mask_words) keep_mask[row * mask_words + widx] = word;
-
-        if (apply && valid) {
-            cur.apply(keep);
-            if (VEC) cur.store_vec(W, row * ldw + q0);
-            else cur.store_elems(W, row * ldw + q0, valid);
-        }
-        cur = nxt;
     }
 
     if (row_pruned != nullptr) {

@@ -10,10 +10,11 @@
 // resident workgroups lower the achieved HBM rate).  Every lane keeps fp32
 // running sums for the columns of its unit, eight rows in flight, four
 // independent accumulator sets so no serial fp32 chain exceeds a quarter of the
-// range.  Each workgroup writes one partial row; a second small kernel adds the
-// partial rows in fp64 in a fixed order (LDS-staged), reduces S, and its last
-// workgroup to finish derives the factor for every channel.  No floating-point
-// atomics: results do not depend on scheduling.
+// range.  Each workgroup writes one partial row segment and the fp64 sum of it;
+// a second small kernel adds the partial rows of every column in fp64 in a fixed
+// order (LDS-staged), adds the per-workgroup sums in index order to get S (every
+// workgroup redoes that small sum, so none waits for another) and writes the
+// factor.  No atomics, no fences: results do not depend on scheduling.
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -23,7 +24,7 @@ constexpr int kStatsThreads = 256;       // one wide strip per workgroup, 4 wave
 constexpr int kStatsUnroll = 8;          // rows (independent 16-byte loads) in flight per lane
 constexpr int kStatsSets = 4;            // independent accumulator sets per column
 constexpr int kStatsTargetGroups = 256;  // one workgroup per compute unit
-constexpr int kCombineThreads = 1024;    // 64 columns x 16 groups of partial rows
+constexpr int kCombineThreads = 256;     // 64 columns x 4 groups of partial rows
 constexpr int kCombineGroups = kCombineThreads / 64;
 
 template <int DT, int EPU>
@@ -80,19 +81,32 @@ struct XUnit<kF32, 1> {
     __device__ __forceinline__ void sq_add(float* a) const { a[0] = fmaf(r, r, a[0]); }
 };
 
+// Sum of a double over the 256 threads of a workgroup, fixed shape: lane tree
+// inside each wavefront, then the four wavefront totals in order.  All threads
+// must call it; every thread gets the result.
+__device__ __forceinline__ double block_sum_256(double v, double* lds4) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, kWave);
+    if ((threadIdx.x & (kWave - 1)) == 0) lds4[threadIdx.x >> 6] = v;
+    __syncthreads();
+    const double t = ((lds4[0] + lds4[1]) + lds4[2]) + lds4[3];
+    __syncthreads();
+    return t;
+}
+
 // grid = (nstrips, splits), block = 256.
 // partials[split * in_pad + u*EPU + k] = sum over the workgroup's token range of X[t, u*EPU + k]^2
-// for the units u of its strip (in_pad = units * EPU).
+// for the units u of its strip (in_pad = units * EPU);
+// group_sums[strip * splits + split] = fp64 sum of that partial row segment (its share of S).
 template <int DT, int EPU>
-__global__ __launch_bounds__(kStatsThreads) void stats_partial_kernel(
+__global__ __launch_bounds__(kStatsThreads) __attribute__((amdgpu_waves_per_eu(1, 2))) void stats_partial_kernel(
     const void* __restrict__ X, int64_t tokens, int64_t units, int strip_units, int64_t ldx,
-    int64_t rows_per_split, float* __restrict__ partials, unsigned int* __restrict__ counters) {
+    int64_t rows_per_split, float* __restrict__ partials, double* __restrict__ group_sums) {
+    __shared__ double lds4[4];
     const int strip = blockIdx.x;
     const int split = blockIdx.y;
-    if (strip == 0 && split == 0 && threadIdx.x == 0) counters[0] = 0u;  // ticket of the combine kernel
-
     const int64_t u = (int64_t)strip * strip_units + threadIdx.x;
-    if ((int)threadIdx.x >= strip_units || u >= units) return;
+    const bool active = (int)threadIdx.x < strip_units && u < units;
     const int64_t col = u * EPU;
     const int64_t r_begin = (int64_t)split * rows_per_split;
     const int64_t r_end = min(tokens, r_begin + rows_per_split);
@@ -103,23 +117,32 @@ __global__ __launch_bounds__(kStatsThreads) void stats_partial_kernel(
 #pragma unroll
         for (int k = 0; k < EPU; ++k) acc[s][k] = 0.f;
 
-    int64_t r = r_begin;
-    for (; r + kStatsUnroll <= r_end; r += kStatsUnroll) {
-        XUnit<DT, EPU> v[kStatsUnroll];
+    double lane_total = 0.0;
+    if (active) {
+        int64_t r = r_begin;
+        for (; r + kStatsUnroll <= r_end; r += kStatsUnroll) {
+            XUnit<DT, EPU> v[kStatsUnroll];
 #pragma unroll
-        for (int j = 0; j < kStatsUnroll; ++j) v[j].load(X, (r + j) * ldx + col);
+            for (int j = 0; j < kStatsUnroll; ++j) v[j].load(X, (r + j) * ldx + col);
 #pragma unroll
-        for (int j = 0; j < kStatsUnroll; ++j) v[j].sq_add(acc[j % kStatsSets]);
+            for (int j = 0; j < kStatsUnroll; ++j) v[j].sq_add(acc[j % kStatsSets]);
+        }
+        for (; r < r_end; ++r) {
+            XUnit<DT, EPU> v;
+            v.load(X, r * ldx + col);
+            v.sq_add(acc[0]);
+        }
+        float* p = partials + (int64_t)split * (units * EPU) + col;
+#pragma unroll
+        for (int k = 0; k < EPU; ++k) {
+            const float t = (acc[0][k] + acc[1][k]) + (acc[2][k] + acc[3][k]);
+            // element-wise path: the last unit may hold columns past `in`; they were never loaded
+            p[k] = t;
+            lane_total += (double)t;
+        }
     }
-    for (; r < r_end; ++r) {
-        XUnit<DT, EPU> v;
-        v.load(X, r * ldx + col);
-        v.sq_add(acc[0]);
-    }
-
-    float* p = partials + (int64_t)split * (units * EPU) + col;
-#pragma unroll
-    for (int k = 0; k < EPU; ++k) p[k] = (acc[0][k] + acc[1][k]) + (acc[2][k] + acc[3][k]);
+    const double total = block_sum_256(lane_total, lds4);
+    if (threadIdx.x == 0) group_sums[(int64_t)strip * gridDim.y + split] = total;
 }
 
 // hr = 1/2 / (1 - xsq/S): three fp32 roundings (divide, subtract, divide).
@@ -132,98 +155,66 @@ __device__ __forceinline__ float channel_factor(float xsq, float S) {
     return __fdiv_rn(0.5f, den);
 }
 
-// grid = ceil(in / 64), block = 1024: thread (c = tid & 63, g = tid >> 6) adds the partial rows
-// s = g, g+16, ... of column blockIdx.x*64 + c in fp64; the sixteen groups are added in order
-// through LDS.  Every workgroup also leaves the fp64 sum of its 64 columns in s_part; the last
-// workgroup to finish adds those in order (= S) and writes the factor for all channels.
+// grid = ceil(in / 64), block = 256: thread (c = tid & 63, g = tid >> 6) adds the partial rows
+// s = g, g+4, ... of column blockIdx.x*64 + c in fp64; the four groups are added in order through
+// LDS.  Every workgroup also adds the streaming kernel's per-workgroup sums in index order, so all
+// of them hold the same S without talking to each other, and writes the factor of its 64 columns.
 __global__ __launch_bounds__(kCombineThreads) void stats_combine_kernel(
-    const float* __restrict__ partials, int splits, int64_t in_pad, int64_t in, float* xsq,
-    int accumulate, int finalize, float* __restrict__ S_out, float* __restrict__ hr,
-    unsigned int* __restrict__ counters, double* s_part) {
+    const float* __restrict__ partials, int splits, int64_t in_pad, int64_t in,
+    const double* __restrict__ group_sums, int ngroups, float* __restrict__ xsq, int accumulate,
+    int finalize, float* __restrict__ S_io, float* __restrict__ hr) {
     __shared__ double part[kCombineGroups][64];
-    __shared__ double colsum[64];
-    __shared__ double red[kCombineThreads / 64];
-    __shared__ unsigned int ticket;
-    __shared__ float S_sh;
+    __shared__ double lds4[4];
 
     const int c = threadIdx.x & 63;
     const int g = threadIdx.x >> 6;
     const int64_t col = (int64_t)blockIdx.x * 64 + c;
 
+    // S of this call: the same fixed-order sum in every workgroup
+    double gs = 0.0;
+    for (int i = threadIdx.x; i < ngroups; i += kCombineThreads) gs += group_sums[i];
+    double S_d = block_sum_256(gs, lds4);
+    if (accumulate) S_d += (double)S_io[0];
+    const float S = (float)S_d;
+
     double s = 0.0;
     if (col < in) {
         const float* p = partials + col;
         int sp = g;
-        for (; sp + 3 * kCombineGroups < splits; sp += 4 * kCombineGroups) {
-            const float a0 = p[(int64_t)sp * in_pad];
-            const float a1 = p[(int64_t)(sp + kCombineGroups) * in_pad];
-            const float a2 = p[(int64_t)(sp + 2 * kCombineGroups) * in_pad];
-            const float a3 = p[(int64_t)(sp + 3 * kCombineGroups) * in_pad];
-            s += (double)a0;
-            s += (double)a1;
-            s += (double)a2;
-            s += (double)a3;
+        for (; sp + 7 * kCombineGroups < splits; sp += 8 * kCombineGroups) {
+            float a[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) a[j] = p[(int64_t)(sp + j * kCombineGroups) * in_pad];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) s += (double)a[j];
         }
         for (; sp < splits; sp += kCombineGroups) s += (double)p[(int64_t)sp * in_pad];
     }
     part[g][c] = s;
     __syncthreads();
-    if (g == 0) {
-        double t = 0.0;
-#pragma unroll
-        for (int i = 0; i < kCombineGroups; ++i) t += part[i][c];
-        float x = 0.f;
-        if (col < in) {
-            if (accumulate) t += (double)xsq[col];
-            x = (float)t;
-            xsq[col] = x;
-        }
-        colsum[c] = (double)x;  // S is the sum of the rounded per-channel values
+    if (g == 0 && col < in) {
+        double t = ((part[0][c] + part[1][c]) + part[2][c]) + part[3][c];
+        if (accumulate) t += (double)xsq[col];
+        const float x = (float)t;
+        xsq[col] = x;
+        if (finalize) hr[col] = channel_factor(x, S);
     }
-    if (!finalize) return;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        double t = 0.0;
-        for (int i = 0; i < 64; ++i) t += colsum[i];
-        s_part[blockIdx.x] = t;
-        __threadfence();  // publish s_part (and this workgroup's xsq) before taking the ticket
-        ticket = atomicAdd(&counters[0], 1u);
-    }
-    __syncthreads();
-    if (ticket != gridDim.x - 1) return;
-    __threadfence();
+    // when accumulating, every workgroup reads the old S_io above, so the new value is stored by a
+    // separate launch; otherwise nobody reads it and workgroup 0 stores it here
+    if (!accumulate && blockIdx.x == 0 && threadIdx.x == 0) S_io[0] = S;
+}
 
-    // last workgroup: S = sum of the per-workgroup sums, in index order
-    const volatile double* sp_v = s_part;
-    const int nblk = (int)gridDim.x;
-    double t = 0.0;
-    for (int i = threadIdx.x; i < nblk; i += kCombineThreads) t += sp_v[i];
-    // fixed-shape tree: within a wavefront by lane halving, then across wavefronts in order
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) t += __shfl_down(t, off, kWave);
-    if (c == 0) red[g] = t;
-    __syncthreads();
+// S[0] <- (accumulate ? S[0] : 0) + sum of the per-workgroup sums; same order as in the combine kernel
+__global__ __launch_bounds__(kCombineThreads) void stats_total_kernel(const double* __restrict__ group_sums,
+                                                                     int ngroups, int accumulate,
+                                                                     float* __restrict__ S_io) {
+    __shared__ double lds4[4];
+    double gs = 0.0;
+    for (int i = threadIdx.x; i < ngroups; i += kCombineThreads) gs += group_sums[i];
+    double S_d = block_sum_256(gs, lds4);
     if (threadIdx.x == 0) {
-        double tot = 0.0;
-        for (int i = 0; i < kCombineThreads / 64; ++i) tot += red[i];
-        S_sh = (float)tot;
-        S_out[0] = S_sh;
-    }
-    __syncthreads();
-    const float S = S_sh;
-    const volatile float* xs = xsq;  // written by other workgroups of this launch
-    for (int64_t q0 = threadIdx.x; q0 < in; q0 += 4 * kCombineThreads) {
-        float x[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int64_t q = q0 + (int64_t)j * kCombineThreads;
-            x[j] = (q < in) ? xs[q] : 0.f;
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int64_t q = q0 + (int64_t)j * kCombineThreads;
-            if (q < in) hr[q] = channel_factor(x[j], S);
-        }
+        if (accumulate) S_d += (double)S_io[0];
+        S_io[0] = (float)S_d;
     }
 }
 
@@ -251,17 +242,20 @@ StatsPlan make_stats_plan(int64_t tokens, int64_t in, int dt, bool vec) {
     return p;
 }
 
+static inline size_t group_sum_bytes(const StatsPlan& p) {
+    return (size_t)ceil_div((int64_t)p.nstrips * p.splits * 8, 256) * 256;
+}
+
 size_t stats_workspace_bytes(const StatsPlan& p) {
-    return kStatsHeaderBytes + (size_t)ceil_div(p.combine_groups * 8, 256) * 256 +
-           p.partial_floats * sizeof(float);
+    return kStatsHeaderBytes + group_sum_bytes(p) + p.partial_floats * sizeof(float);
 }
 
 template <int DT, int EPU>
 static hipError_t launch_partial(const void* X, int64_t tokens, int64_t ldx, const StatsPlan& p,
-                                 float* partials, unsigned int* counters, hipStream_t stream) {
+                                 float* partials, double* group_sums, hipStream_t stream) {
     dim3 grid((unsigned)p.nstrips, (unsigned)p.splits);
     hipLaunchKernelGGL((stats_partial_kernel<DT, EPU>), grid, dim3(kStatsThreads), 0, stream, X, tokens,
-                       p.units, p.strip_units, ldx, p.rows_per_split, partials, counters);
+                       p.units, p.strip_units, ldx, p.rows_per_split, partials, group_sums);
     return hipGetLastError();
 }
 
@@ -270,21 +264,24 @@ hipError_t launch_layer_stats(const void* X, int64_t tokens, int64_t in, int64_t
                               void* workspace, hipStream_t stream) {
     const StatsPlan p = make_stats_plan(tokens, in, dt, vec);
     char* ws = static_cast<char*>(workspace);
-    unsigned int* counters = reinterpret_cast<unsigned int*>(ws);
-    double* s_part = reinterpret_cast<double*>(ws + kStatsHeaderBytes);
-    float* partials =
-        reinterpret_cast<float*>(ws + kStatsHeaderBytes + (size_t)ceil_div(p.combine_groups * 8, 256) * 256);
+    double* group_sums = reinterpret_cast<double*>(ws + kStatsHeaderBytes);
+    float* partials = reinterpret_cast<float*>(ws + kStatsHeaderBytes + group_sum_bytes(p));
     hipError_t e;
     if (dt == kBF16)
-        e = vec ? launch_partial<kBF16, 8>(X, tokens, ldx, p, partials, counters, stream)
-                : launch_partial<kBF16, 1>(X, tokens, ldx, p, partials, counters, stream);
+        e = vec ? launch_partial<kBF16, 8>(X, tokens, ldx, p, partials, group_sums, stream)
+                : launch_partial<kBF16, 1>(X, tokens, ldx, p, partials, group_sums, stream);
     else
-        e = vec ? launch_partial<kF32, 4>(X, tokens, ldx, p, partials, counters, stream)
-                : launch_partial<kF32, 1>(X, tokens, ldx, p, partials, counters, stream);
+        e = vec ? launch_partial<kF32, 4>(X, tokens, ldx, p, partials, group_sums, stream)
+                : launch_partial<kF32, 1>(X, tokens, ldx, p, partials, group_sums, stream);
     if (e != hipSuccess) return e;
+    const int ngroups = p.nstrips * p.splits;
     hipLaunchKernelGGL(stats_combine_kernel, dim3((unsigned)p.combine_groups), dim3(kCombineThreads), 0,
-                       stream, partials, p.splits, p.units * p.epu, in, xsq, accumulate, finalize, S, hr,
-                       counters, s_part);
+                       stream, partials, p.splits, p.units * p.epu, in, group_sums, ngroups, xsq,
+                       accumulate, finalize, S, hr);
+    e = hipGetLastError();
+    if (e != hipSuccess || !accumulate) return e;
+    hipLaunchKernelGGL(stats_total_kernel, dim3(1), dim3(kCombineThreads), 0, stream, group_sums, ngroups,
+                       accumulate, S);
     return hipGetLastError();
 }
 
