@@ -38,6 +38,9 @@ def parse():
     ap.add_argument("--tokens", type=int, default=128 * 2048)
     ap.add_argument("--shared-stats", action="store_true",
                     help="compute statistics once per distinct layer input (q/k/v and gate/up share)")
+    ap.add_argument("--streams", type=int, default=1, choices=[1, 2],
+                    help="2 = statistics on one stream, selection+apply on another (double-buffered factors), "
+                         "so a layer's selection overlaps the next layer's statistics")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not bracket the statistics launches with events")
@@ -85,34 +88,47 @@ def main():
     for name, out, n in block:
         if (out, n) not in bufs:
             bufs[(out, n)] = sp.LayerBuffers(out, n, T, dev)
+    # one plain copy of known size for calibrating the HBM byte counters of a profiler run: the apply
+    # kernel with an all-ones keep mask reads and rewrites an 8192 x 8192 bf16 matrix (128 MiB each way,
+    # plus 8 MiB of mask) with the same 16-byte non-temporal loads as the timed kernels
+    cal_W = torch.zeros((8192, 8192), dtype=torch.bfloat16, device=dev)
+    cal_mask = torch.full((8192, 256), -1, dtype=torch.int32, device=dev)
+    sp.swiftprune_apply(cal_W, cal_mask)
     torch.cuda.synchronize()
+    del cal_W, cal_mask
     setup_s = time.time() - t_setup
 
     w_bytes = sum(out * n * 2 for _, out, n in layers)
     n_weights = sum(out * n for _, out, n in layers)
-    stats_calls = [(name, n) for name, _, n in layers]
     if args.shared_stats:
-        seen_per_block = []
-        stats_bytes = 0
-        for bi in range(args.blocks):
-            stats_bytes += sum(T * n * 2 for n in [widths[k] for k in sorted(widths)])
+        stats_bytes = args.blocks * sum(T * n * 2 for n in widths.values())
     else:
-        stats_bytes = sum(T * n * 2 for _, n in stats_calls)
+        stats_bytes = sum(T * n * 2 for _, _, n in layers)
     # select + apply fused: W read, W written, mask written, factor read
     select_bytes = sum(out * n * 2 * 2 + out * n // 8 + n * 4 for _, out, n in layers)
     algo_bytes = stats_bytes + select_bytes
 
     stream = torch.cuda.current_stream()
+    side = torch.cuda.Stream(device=dev) if args.streams == 2 else None
     ev_pairs = []       # (start, stop, bytes) around statistics launches of timed steps
+    # with two streams every layer shape has two sets of (xsq, S, hr, workspace, mask) used alternately
+    bufs2 = {k: sp.LayerBuffers(k[0], k[1], T, dev) for k in bufs} if side is not None else None
 
     def step(record):
         idx = 0
+        use = {}            # (out, n) -> parity of the buffer set to use next
+        sel_done = {}       # buffer set id -> event recorded after the selection that last read it
         for bi in range(args.blocks):
             done_inputs = set()
             for name, out, n in block:
                 W = weights[idx]
                 idx += 1
-                b = bufs[(out, n)]
+                par = use.get((out, n), 0)
+                b = bufs[(out, n)] if (side is None or par == 0) else bufs2[(out, n)]
+                if side is not None:
+                    use[(out, n)] = par ^ 1
+                    if id(b) in sel_done:              # statistics may not overwrite hr while it is read
+                        stream.wait_event(sel_done[id(b)])
                 key = INPUT_OF[name]
                 if not (args.shared_stats and key in done_inputs):
                     if record:
@@ -126,14 +142,27 @@ def main():
                     done_inputs.add(key)
                     if args.shared_stats:
                         # keep the factor of this input for the layers that share it
-                        shared_hr[key].copy_(b.hr)
+                        with torch.cuda.stream(stream):
+                            shared_hr[key].copy_(b.hr)
                 hr = shared_hr[key] if args.shared_stats else b.hr
+                sel_stream = stream
+                if side is not None:
+                    ready = torch.cuda.Event()
+                    ready.record(stream)
+                    side.wait_event(ready)
+                    sel_stream = side
                 if nm is None:
                     sp.swiftprune_score_select(W, hr, b.keep_mask, la=la, row_pruned=b.row_pruned,
-                                               flags=sp.SP_APPLY_INPLACE, stream=stream)
+                                               flags=sp.SP_APPLY_INPLACE, stream=sel_stream)
                 else:
                     sp.swiftprune_nm_select(W, hr, nm[0], nm[1], b.keep_mask, flags=sp.SP_APPLY_INPLACE,
-                                            stream=stream)
+                                            stream=sel_stream)
+                if side is not None:
+                    done = torch.cuda.Event()
+                    done.record(side)
+                    sel_done[id(b)] = done
+        if side is not None:
+            stream.wait_stream(side)                   # the step ends when both streams have drained
 
     shared_hr = {key: torch.empty(n, dtype=torch.float32, device=dev) for key, n in widths.items()}
 
@@ -168,8 +197,10 @@ def main():
         b = bufs[(block[-1][1], block[-1][2])]
         pruned_frac = float(b.row_pruned.sum().item()) / (block[-1][1] * block[-1][2])
 
-    roofline = {"bound": "hbm", "kernel": "stats_partial_kernel (swiftprune_layer_stats)",
-                "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None, "traffic": None}
+    roofline = {"bound": "hbm",
+                "kernel": "stats_partial_kernel (events bracket swiftprune_layer_stats = it + the 4 us combine kernel)",
+                "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None,
+                "traffic": committed_traffic()}
     if ev_pairs:
         tot_ms = sum(a.elapsed_time(b) for a, b, _ in ev_pairs)
         tot_bytes = sum(nb for _, _, nb in ev_pairs)
@@ -196,7 +227,7 @@ def main():
                                f"{T} calibration tokens per layer, "
                                + ("50% unstructured (la=0.5)" if nm is None else f"{args.mode} structured"),
                    "storage": "bf16", "tokens": T, "blocks": args.blocks, "mode": args.mode,
-                   "stats_calls_per_block": 4 if args.shared_stats else 7,
+                   "stats_calls_per_block": 4 if args.shared_stats else 7, "streams": args.streams,
                    "weights": n_weights},
         "seconds_per_model": round(ms_per_step * 1e-3, 5),
         "step_ms_min_max": [round(min(step_ms), 3), round(max(step_ms), 3)],
@@ -214,6 +245,29 @@ def main():
         result["cpu_baseline"] = cpu_baseline(block, X, pristine, T, nm, la)
 
     print(json.dumps(result))
+
+
+def committed_traffic():
+    """HBM bytes per launch of the statistics kernel from the committed counter runs
+    (profiles/stats_partial_kernel_llama3_8b_pmc.txt); None when the kernel source has changed since."""
+    import hashlib
+    path = os.path.join(ROOT, "profiles", "stats_partial_kernel_llama3_8b_pmc.txt")
+    if not os.path.exists(path):
+        return None
+    kv = {}
+    for line in open(path):
+        if "=" in line and not line.lstrip().startswith("#"):
+            k, v = line.split("=", 1)
+            kv[k.strip()] = v.strip()
+    h = hashlib.sha256()
+    for f in ("stats.hip", "common.hpp"):
+        h.update(open(os.path.join(ROOT, "paper_2501_16376_amd", "csrc", f), "rb").read())
+    if kv.get("kernel_source_sha256") != h.hexdigest():
+        return None
+    try:
+        return int(float(kv["traffic_bytes_per_launch_avg"]))
+    except (KeyError, ValueError):
+        return None
 
 
 def cpu_baseline(block, X, pristine, T, nm, la):
