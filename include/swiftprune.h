@@ -40,7 +40,9 @@ typedef enum {
     SP_OK = 0,
     SP_EINVAL = -1, /* bad argument (null pointer, non-positive size, pitch < columns, unknown dtype or pattern, ...) */
     SP_ENOSPC = -2, /* workspace smaller than swiftprune_stats_workspace_bytes() */
-    SP_EHIP = -3    /* the HIP runtime refused a launch; hipGetLastError() has the code */
+    SP_EHIP = -3,   /* the HIP runtime refused a launch; hipGetLastError() has the code */
+    SP_ERANGE = -4  /* swiftprune_calibrate_la: the target ratio is not reachable within the tolerance
+                       (outputs hold the closest candidate found) */
 } sp_status;
 
 /* EWMA parameters of Algorithm 1.  alpha, beta in (0, 1];  la is the
@@ -111,6 +113,35 @@ int swiftprune_score_select(const void *W, int64_t out, int64_t in, int64_t ldw,
                             const float *hr, float sparsity, const sp_ewma_params *params,
                             uint32_t *keep_mask, int32_t *row_pruned, float *scores,
                             uint32_t flags, void *hip_stream);
+
+/*
+ * Threshold tuning (Sec. 3.1: the ratio -> la table covers 50..90 % only and "la can be tuned for
+ * different levels of sparsity").  With S fixed, est and dev do not depend on la, so one pass over W
+ * counts the pruned weights for several candidate la at once.
+ *
+ *   la       host array of n_la (1..16) finite candidates
+ *   counts   [n_la] uint64, overwritten: counts[i] = number of weights of the whole matrix with
+ *            L < est - la[i]*dev (scan evaluation, as in swiftprune_score_select)   (device, write)
+ * Asynchronous on hip_stream like the other entry points.
+ */
+int swiftprune_count_pruned(const void *W, int64_t out, int64_t in, int64_t ldw, sp_dtype dt,
+                            const float *hr, float alpha, float beta, const float *la, int n_la,
+                            unsigned long long *counts, void *hip_stream);
+
+/*
+ * Searches la in [la_lo, la_hi] so that the pruned fraction of W is within `tolerance` of
+ * `target_sparsity` (the fraction is non-increasing in la): up to 8 passes of 16 equally spaced
+ * candidates, each pass one counting launch and one 128-byte copy to the host.
+ * UNLIKE the other entry points this call SYNCHRONISES hip_stream before it returns.
+ *
+ *   counts_ws  device scratch, >= 16 uint64 (128 bytes), 8-byte aligned
+ *   la, achieved   host out-arguments: the chosen la and the pruned fraction it gives
+ * Returns SP_OK, or SP_ERANGE when no candidate came within the tolerance (outputs = the closest).
+ */
+int swiftprune_calibrate_la(const void *W, int64_t out, int64_t in, int64_t ldw, sp_dtype dt,
+                            const float *hr, float alpha, float beta, float target_sparsity,
+                            float tolerance, float la_lo, float la_hi, unsigned long long *counts_ws,
+                            float *la, float *achieved, void *hip_stream);
 
 /*
  * Steps 2+3, structured N:M (Sec. 3.3): in every group of m_group consecutive

@@ -74,12 +74,13 @@ def _declare(L: C.CDLL) -> C.CDLL:
     L.oracle_nm_select_f64.argtypes = [_vp, _i64, _i64, _i64, _i32, _vp, _i32, _i32, _vp, _vp]
     L.oracle_ewma_select_literal_f32.argtypes = [_vp, _i64, _i64, _i64, _i32, _vp, _f, _f, _f, _f,
                                                  _vp, _vp, _vp]
+    L.oracle_topk_select_f32.argtypes = [_vp, _i64, _i64, _i64, _i32, _vp, _vp, _i64, _vp]
     L.oracle_apply.argtypes = [_vp, _i64, _i64, _i64, _i32, _vp]
     for name in ("oracle_stats_accumulate", "oracle_stats_finalize", "oracle_channel_factor_f32",
                  "oracle_channel_factor_f64", "oracle_score_f32", "oracle_score_f64",
                  "oracle_ewma_row_f32", "oracle_ewma_row_f64", "oracle_ewma_select_f32",
                  "oracle_ewma_select_f64", "oracle_nm_select_f32", "oracle_nm_select_f64",
-                 "oracle_ewma_select_literal_f32", "oracle_apply"):
+                 "oracle_ewma_select_literal_f32", "oracle_topk_select_f32", "oracle_apply"):
         getattr(L, name).restype = None
     return L
 
@@ -222,6 +223,21 @@ def nm_select(W: np.ndarray, hr: np.ndarray, n_keep: int, m_group: int, precisio
     getattr(L or lib(), "oracle_nm_select" + sfx)(ptr, out, n, ld, dt, hr.ctypes.data, n_keep, m_group,
                                                   mask.ctypes.data, _p(sc))
     return mask, sc
+
+
+def topk_select(W: np.ndarray, hr: np.ndarray, k, L=None) -> np.ndarray:
+    """Exact sort-based selection: prune the k smallest scores of every row (k: int or int32[out])."""
+    ptr, out, n, ld, dt = _mat(W)
+    hr = np.ascontiguousarray(hr, dtype=np.float32)
+    mask = np.empty((out, (n + 31) // 32), dtype=np.uint32)
+    if np.isscalar(k):
+        kp, ku = None, int(k)
+    else:
+        karr = np.ascontiguousarray(k, dtype=np.int32)
+        assert karr.shape == (out,)
+        kp, ku = karr.ctypes.data, 0
+    (L or lib()).oracle_topk_select_f32(ptr, out, n, ld, dt, hr.ctypes.data, kp, ku, mask.ctypes.data)
+    return mask
 
 
 # ---------------------------------------------------------------- step 5

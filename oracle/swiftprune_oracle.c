@@ -222,6 +222,57 @@ void oracle_ewma_select_literal_f32(const void *W, int64_t out, int64_t in, int6
 }
 
 /* ------------------------------------------------------------------ */
+/* Exact selection by sorting (Sec. 3.1: "sort the L values of all      */
+/* weights and eliminate those with the smallest L values") - the       */
+/* O(n log n) rule the EWMA walk replaces; used as a comparator.        */
+/* ------------------------------------------------------------------ */
+
+typedef struct {
+    float score;
+    int64_t index;
+} scored_t;
+
+static int scored_cmp(const void *a, const void *b)
+{
+    const scored_t *x = (const scored_t *)a, *y = (const scored_t *)b;
+    if (x->score < y->score) return -1;
+    if (x->score > y->score) return 1;
+    return (x->index > y->index) - (x->index < y->index); /* equal scores: lower index first */
+}
+
+/*
+ * Per row r: sort (L, index) ascending and prune the first k_r entries, where
+ * k_r = k_per_row[r] if k_per_row != NULL, else k_uniform (clamped to [0, in]).
+ * NaN scores are ordered after everything else (never pruned before a number).
+ */
+void oracle_topk_select_f32(const void *W, int64_t out, int64_t in, int64_t ldw, int dt,
+                            const float *hr, const int32_t *k_per_row, int64_t k_uniform,
+                            uint32_t *keep_mask)
+{
+    const int64_t words = (in + 31) / 32;
+    float *L = (float *)malloc((size_t)in * sizeof(float));
+    scored_t *s = (scored_t *)malloc((size_t)in * sizeof(scored_t));
+    for (int64_t r = 0; r < out; ++r) {
+        score_row_f32(W, dt, r * ldw, in, hr, L);
+        for (int64_t q = 0; q < in; ++q) {
+            s[q].score = (L[q] != L[q]) ? INFINITY : L[q];
+            s[q].index = (L[q] != L[q]) ? q + in : q;   /* NaN after +inf, in index order */
+        }
+        qsort(s, (size_t)in, sizeof(scored_t), scored_cmp);
+        int64_t k = k_per_row ? (int64_t)k_per_row[r] : k_uniform;
+        if (k < 0) k = 0;
+        if (k > in) k = in;
+        for (int64_t w = 0; w < words; ++w) keep_mask[r * words + w] = 0u;
+        for (int64_t j = k; j < in; ++j) {
+            int64_t q = s[j].index >= in ? s[j].index - in : s[j].index;
+            keep_mask[r * words + (q >> 5)] |= (uint32_t)1 << (q & 31);
+        }
+    }
+    free(L);
+    free(s);
+}
+
+/* ------------------------------------------------------------------ */
 /* Step 5: apply (Algorithm 1: w_i = 0 for pruned entries, c_i = w_i).  */
 /* ------------------------------------------------------------------ */
 

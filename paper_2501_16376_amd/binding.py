@@ -16,11 +16,11 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libswiftprune.so")
 
 SP_F32, SP_BF16 = 0, 1
-SP_OK, SP_EINVAL, SP_ENOSPC, SP_EHIP = 0, -1, -2, -3
+SP_OK, SP_EINVAL, SP_ENOSPC, SP_EHIP, SP_ERANGE = 0, -1, -2, -3, -4
 SP_SEQUENTIAL_ORDER, SP_APPLY_INPLACE = 1, 2
 
 EXPORTS = ("swiftprune_layer_stats", "swiftprune_score_select", "swiftprune_nm_select",
-           "swiftprune_apply", "swiftprune_la_for_sparsity", "swiftprune_stats_workspace_bytes",
+           "swiftprune_apply", "swiftprune_count_pruned", "swiftprune_calibrate_la", "swiftprune_la_for_sparsity", "swiftprune_stats_workspace_bytes",
            "swiftprune_strerror", "swiftprune_version")
 
 
@@ -57,6 +57,11 @@ def load_library(path: str | None = None) -> C.CDLL:
     L.swiftprune_nm_select.restype = i32
     L.swiftprune_apply.argtypes = [vp, i64, i64, i64, i32, vp, vp]
     L.swiftprune_apply.restype = i32
+    L.swiftprune_count_pruned.argtypes = [vp, i64, i64, i64, i32, vp, f, f, C.POINTER(C.c_float), i32, vp, vp]
+    L.swiftprune_count_pruned.restype = i32
+    L.swiftprune_calibrate_la.argtypes = [vp, i64, i64, i64, i32, vp, f, f, f, f, f, f, vp,
+                                          C.POINTER(C.c_float), C.POINTER(C.c_float), vp]
+    L.swiftprune_calibrate_la.restype = i32
     L.swiftprune_la_for_sparsity.argtypes = [f, C.POINTER(C.c_float)]
     L.swiftprune_la_for_sparsity.restype = i32
     L.swiftprune_stats_workspace_bytes.argtypes = [i64, i64]
@@ -173,6 +178,38 @@ def swiftprune_nm_select(W, hr, n_keep: int, m_group: int, keep_mask, scores=Non
         _vec(keep_mask, torch.int32, out * words, "keep_mask"),
         _vec(scores, torch.float32, out * n_in, "scores"), int(flags), _stream(stream))
     _check(code, "swiftprune_nm_select")
+
+
+def swiftprune_count_pruned(W, hr, la_candidates, counts, alpha: float = 0.125, beta: float = 0.125,
+                            stream=None):
+    """counts[i] (int64 GPU tensor, >= len(la_candidates)) = weights pruned with la_candidates[i]."""
+    import torch
+    ptr, out, n_in, ldw, dt = _matrix(W)
+    n = len(la_candidates)
+    arr = (C.c_float * n)(*[float(x) for x in la_candidates])
+    code = load_library().swiftprune_count_pruned(
+        ptr, out, n_in, ldw, dt, _vec(hr, torch.float32, n_in, "hr"), float(alpha), float(beta), arr, n,
+        _vec(counts, torch.int64, n, "counts"), _stream(stream))
+    _check(code, "swiftprune_count_pruned")
+
+
+def swiftprune_calibrate_la(W, hr, target_sparsity: float, tolerance: float = 1e-3, la_lo: float = -8.0,
+                            la_hi: float = 8.0, alpha: float = 0.125, beta: float = 0.125, counts_ws=None,
+                            stream=None):
+    """(la, achieved, reached) with the pruned fraction of W within `tolerance` of the target when
+    reached is True.  Synchronises the stream."""
+    import torch
+    ptr, out, n_in, ldw, dt = _matrix(W)
+    if counts_ws is None:
+        counts_ws = torch.empty(16, dtype=torch.int64, device=W.device)
+    la, ach = C.c_float(), C.c_float()
+    code = load_library().swiftprune_calibrate_la(
+        ptr, out, n_in, ldw, dt, _vec(hr, torch.float32, n_in, "hr"), float(alpha), float(beta),
+        float(target_sparsity), float(tolerance), float(la_lo), float(la_hi),
+        _vec(counts_ws, torch.int64, 16, "counts_ws"), C.byref(la), C.byref(ach), _stream(stream))
+    if code not in (SP_OK, SP_ERANGE):
+        _check(code, "swiftprune_calibrate_la")
+    return la.value, ach.value, code == SP_OK
 
 
 def swiftprune_apply(W, keep_mask, stream=None):

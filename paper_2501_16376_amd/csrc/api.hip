@@ -41,6 +41,7 @@ const char* swiftprune_strerror(int code) {
         case SP_EINVAL: return "invalid argument";
         case SP_ENOSPC: return "workspace too small";
         case SP_EHIP: return "HIP runtime error (see hipGetLastError)";
+        case SP_ERANGE: return "target not reachable within tolerance; closest value returned";
         default: return "unknown status";
     }
 }
@@ -117,6 +118,46 @@ int swiftprune_score_select(const void* W, int64_t out, int64_t in, int64_t ldw,
                                  apply, stream);
     }
     return e == hipSuccess ? SP_OK : SP_EHIP;
+}
+
+int swiftprune_count_pruned(const void* W, int64_t out, int64_t in, int64_t ldw, sp_dtype dt,
+                            const float* hr, float alpha, float beta, const float* la, int n_la,
+                            unsigned long long* counts, void* hip_stream) {
+    if (W == nullptr || hr == nullptr || la == nullptr || counts == nullptr) return SP_EINVAL;
+    if (out <= 0 || in <= 0 || ldw < in || !dtype_ok((int)dt)) return SP_EINVAL;
+    if (n_la < 1 || n_la > 16) return SP_EINVAL;
+    if (!(alpha > 0.0f && alpha <= 1.0f) || !(beta > 0.0f && beta <= 1.0f)) return SP_EINVAL;
+    for (int i = 0; i < n_la; ++i)
+        if (isnan(la[i]) || isinf(la[i])) return SP_EINVAL;
+    if (reinterpret_cast<uintptr_t>(W) % elem_size((int)dt) != 0) return SP_EINVAL;
+    if (reinterpret_cast<uintptr_t>(counts) % 8 != 0) return SP_EINVAL;
+    const bool vec = weight_vec_ok(W, in, ldw, (int)dt, hr, nullptr);
+    const sp::EwmaConsts c = sp::make_ewma_consts(alpha, beta, 0.0f);
+    const hipError_t e = sp::launch_count_pruned(W, out, in, ldw, (int)dt, vec, hr, c, la, n_la, counts,
+                                                 static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? SP_OK : SP_EHIP;
+}
+
+int swiftprune_calibrate_la(const void* W, int64_t out, int64_t in, int64_t ldw, sp_dtype dt,
+                            const float* hr, float alpha, float beta, float target_sparsity,
+                            float tolerance, float la_lo, float la_hi, unsigned long long* counts_ws,
+                            float* la, float* achieved, void* hip_stream) {
+    if (W == nullptr || hr == nullptr || counts_ws == nullptr || la == nullptr || achieved == nullptr)
+        return SP_EINVAL;
+    if (out <= 0 || in <= 0 || ldw < in || !dtype_ok((int)dt)) return SP_EINVAL;
+    if (!(alpha > 0.0f && alpha <= 1.0f) || !(beta > 0.0f && beta <= 1.0f)) return SP_EINVAL;
+    if (!(target_sparsity > 0.0f && target_sparsity < 1.0f) || !(tolerance > 0.0f)) return SP_EINVAL;
+    if (!(la_lo < la_hi) || isinf(la_lo) || isinf(la_hi)) return SP_EINVAL;
+    if (reinterpret_cast<uintptr_t>(W) % elem_size((int)dt) != 0) return SP_EINVAL;
+    if (reinterpret_cast<uintptr_t>(counts_ws) % 8 != 0) return SP_EINVAL;
+    const bool vec = weight_vec_ok(W, in, ldw, (int)dt, hr, nullptr);
+    const sp::EwmaConsts c = sp::make_ewma_consts(alpha, beta, 0.0f);
+    int status = 1;
+    const hipError_t e = sp::run_calibrate_la(W, out, in, ldw, (int)dt, vec, hr, c, target_sparsity, tolerance,
+                                              la_lo, la_hi, counts_ws, la, achieved, &status,
+                                              static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return SP_EHIP;
+    return status == 0 ? SP_OK : SP_ERANGE;
 }
 
 int swiftprune_nm_select(const void* W, int64_t out, int64_t in, int64_t ldw, sp_dtype dt,

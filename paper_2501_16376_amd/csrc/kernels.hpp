@@ -46,6 +46,15 @@ hipError_t launch_ewma_sequential(const void* W, int64_t out, int64_t in, int64_
                                   uint32_t* keep_mask, int32_t* row_pruned, float* scores, bool apply,
                                   hipStream_t stream);
 
+// ---- threshold calibration (count the pruned weights for up to 16 candidate la in one pass) ----
+hipError_t launch_count_pruned(const void* W, int64_t out, int64_t in, int64_t ldw, int dt, bool vec,
+                               const float* hr, const EwmaConsts& c, const float* la, int n_la,
+                               unsigned long long* counts, hipStream_t stream);
+hipError_t run_calibrate_la(const void* W, int64_t out, int64_t in, int64_t ldw, int dt, bool vec,
+                            const float* hr, const EwmaConsts& c, float target, float tolerance,
+                            float la_lo, float la_hi, unsigned long long* counts_dev, float* la_out,
+                            float* achieved_out, int* status, hipStream_t stream);
+
 // ---- steps 2+3 structured, step 4 ----
 hipError_t launch_nm_select(const void* W, int64_t out, int64_t in, int64_t ldw, int dt, bool vec,
                             const float* hr, int n_keep, int m_group, uint32_t* keep_mask,

@@ -410,7 +410,31 @@ def pin_sort_comparator(orc, L=None):
     return report
 
 
-ALL_PINS = [pin_worked_rows, pin_closed_form, pin_constant_row, pin_first_two_elements,
+def pin_topk_is_library_sort(orc, L=None):
+    """The sort-based comparator equals numpy's lexsort on (score, index): the k smallest go, ties by
+    the lower index, k = 0 and k = in behave, per-row k is honoured."""
+    from paper_2501_16376_amd import synth
+    Wb, Xb = synth.layer_inputs(10, 96, 64, seed=31, dtype="bf16", n_outlier=2)
+    Wb[3, 10:20] = Wb[3, 10]                       # exact ties inside a row
+    Wb[4, :] = Wb[4, 0]                            # a whole row of ties
+    _, _, hr = orc.layer_stats(Xb, L=L)
+    hr[:] = np.float32(hr[0])                      # ties in w must be ties in score
+    sc = orc.score(Wb, hr, L=L)
+    ks = np.array([0, 1, 5, 7, 40, 48, 95, 96, 200, -3], dtype=np.int32)
+    mask = orc.topk_select(Wb, hr, ks, L=L)
+    keep = orc.unpack_mask(mask, 96)
+    for r in range(10):
+        k = int(np.clip(ks[r], 0, 96))
+        order = np.lexsort((np.arange(96), sc[r]))
+        ref = np.ones(96, dtype=bool)
+        ref[order[:k]] = False
+        assert np.array_equal(keep[r], ref), r
+    keep4 = orc.unpack_mask(orc.topk_select(Wb, hr, 40, L=L), 96)
+    assert np.array_equal(keep4[4], np.arange(96) >= 40)          # all-tie row: the first 40 go
+    assert np.all((~keep4).sum(1) == 40)
+
+
+ALL_PINS = [pin_topk_is_library_sort, pin_worked_rows, pin_closed_form, pin_constant_row, pin_first_two_elements,
             pin_monotone_in_la, pin_step_response, pin_stats_library_sum, pin_inverse_identity,
             pin_float_factor_matches_double, pin_select_metamorphic,
             pin_uniform_energy_reduces_to_magnitude, pin_nm_invariants,

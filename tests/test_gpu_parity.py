@@ -252,7 +252,7 @@ def test_all_ones_exact(orc, gpu):
     assert np.all(hr == np.float32(0.5) / (np.float32(1) - np.float32(1 / 1024)))
 
 
-def _full_size_layer(orc, gpu, out, n, seed, sample_cols=None):
+def _full_size_layer(orc, gpu, out, n, seed, sample_cols=None, las=(0.5,)):
     """A Llama-sized layer at the full 128x2048 calibration tokens, in the launch configuration the
     benchmark times.  Statistics: against the oracle on all columns (or a column sample for wide
     layers; S then against the fp64 sum of the GPU's own xsq).  Selection: whole matrix."""
@@ -288,15 +288,17 @@ def _full_size_layer(orc, gpu, out, n, seed, sample_cols=None):
     torch.cuda.empty_cache()
     Wh = synth.torch_to_host_bits(W)
     hr_dev = to_device(hr_o, gpu)
-    say("[full] strict-order selection")
-    mask_o, cnt_o, _ = orc.ewma_select(Wh, hr_o, A, B, 0.5)
-    m_seq, c_seq, _ = _select_gpu(W, hr_dev, 0.5, flags=b.SP_SEQUENTIAL_ORDER)
-    assert np.array_equal(m_seq, mask_o) and np.array_equal(c_seq, cnt_o)
-    say("[full] scan selection")
+    for la in las:
+        say(f"[full] la={la}: strict-order selection")
+        mask_o, cnt_o, _ = orc.ewma_select(Wh, hr_o, A, B, la)
+        m_seq, c_seq, _ = _select_gpu(W, hr_dev, la, flags=b.SP_SEQUENTIAL_ORDER)
+        assert np.array_equal(m_seq, mask_o) and np.array_equal(c_seq, cnt_o)
+        say(f"[full] la={la}: scan selection")
+        m_scan, c_scan, _ = _select_gpu(W, hr_dev, la)
+        t = check_ewma_mask(orc, Wh, hr_o, A, B, la, m_scan, c_scan)
+        say(f"[full] la={la}: scan vs oracle: {t} tolerated differences of {out * n} weights; "
+            f"sparsity {cnt_o.sum() / (out * n):.4f}")
     m_scan, c_scan, _ = _select_gpu(W, hr_dev, 0.5)
-    t = check_ewma_mask(orc, Wh, hr_o, A, B, 0.5, m_scan, c_scan)
-    say(f"[full] scan vs oracle: {t} tolerated differences of {out * n} weights; "
-        f"sparsity {cnt_o.sum() / (out * n):.4f}")
     for nk, m in ((2, 4), (4, 8)):
         nm_o, _ = orc.nm_select(Wh, hr_o, nk, m)
         nm_g, _ = _nm_gpu(W, hr_dev, nk, m)
@@ -330,3 +332,24 @@ def test_full_size_down_8b(orc, gpu):
 
 def test_full_size_down_7b(orc, gpu):
     _full_size_layer(orc, gpu, 4096, 11008, seed=500, sample_cols=192)
+
+
+def test_full_size_gate_7b(orc, gpu):
+    _full_size_layer(orc, gpu, 11008, 4096, seed=600, sample_cols=192)
+
+
+# Llama-2-70B-shaped layers (hidden 8192, intermediate 28672): the table's la for 50 % and 70 %
+def test_full_size_q_proj_70b(orc, gpu):
+    _full_size_layer(orc, gpu, 8192, 8192, seed=700, sample_cols=192, las=(0.5, -0.2))
+
+
+def test_full_size_kv_proj_70b(orc, gpu):
+    _full_size_layer(orc, gpu, 1024, 8192, seed=800, sample_cols=192)
+
+
+def test_full_size_gate_70b(orc, gpu):
+    _full_size_layer(orc, gpu, 28672, 8192, seed=900, sample_cols=192)
+
+
+def test_full_size_down_70b(orc, gpu):
+    _full_size_layer(orc, gpu, 8192, 28672, seed=1000, sample_cols=192, las=(0.5, -0.2))

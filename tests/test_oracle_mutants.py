@@ -39,6 +39,11 @@ MUTANTS = [
     ("S_is_mean", "swiftprune_oracle.c", "*S = (float)s;", "*S = (float)(s / (double)in);"),
     ("bf16_low_half", "swiftprune_oracle.c", "uint32_t u = (uint32_t)b << 16;", "uint32_t u = (uint32_t)b;"),
     ("literal_never_updates_S", "swiftprune_oracle.c", "S_r = S_new;", ""),
+    ("topk_descending", "swiftprune_oracle.c", "if (x->score < y->score) return -1;\n    if (x->score > y->score) return 1;",
+     "if (x->score < y->score) return 1;\n    if (x->score > y->score) return -1;"),
+    ("topk_tie_break_reversed", "swiftprune_oracle.c", "return (x->index > y->index) - (x->index < y->index);",
+     "return (x->index < y->index) - (x->index > y->index);"),
+    ("topk_off_by_one", "swiftprune_oracle.c", "for (int64_t j = k; j < in; ++j) {", "for (int64_t j = k + 1; j < in; ++j) {"),
     ("apply_zeroes_kept", "swiftprune_oracle.c", "if (keep) continue;", "if (!keep) continue;"),
 ]
 
