@@ -144,6 +144,17 @@ int swiftprune_calibrate_la(const void *W, int64_t out, int64_t in, int64_t ldw,
                             float *la, float *achieved, void *hip_stream);
 
 /*
+ * Exact comparator (Sec. 3.1: "sort the L values of all weights and eliminate those with the smallest
+ * L values" - the O(n log n) rule the EWMA walk replaces).  In every row the k smallest scores are
+ * pruned, equal scores in index order; k = k_per_row[r] when k_per_row != NULL (device, int32[out]),
+ * else k_uniform; k is clamped to [0, in].  Implemented as a per-row radix select, no sort.
+ * keep_mask as above; flags: SP_APPLY_INPLACE.  NaN scores rank above every number.
+ */
+int swiftprune_topk_select(const void *W, int64_t out, int64_t in, int64_t ldw, sp_dtype dt,
+                           const float *hr, const int32_t *k_per_row, int64_t k_uniform,
+                           uint32_t *keep_mask, uint32_t flags, void *hip_stream);
+
+/*
  * Steps 2+3, structured N:M (Sec. 3.3): in every group of m_group consecutive
  * inputs of a row keep the n_keep entries of highest score and prune the rest;
  * among equal scores the lower index is pruned first.  Supported: m_group in

@@ -20,7 +20,7 @@ SP_OK, SP_EINVAL, SP_ENOSPC, SP_EHIP, SP_ERANGE = 0, -1, -2, -3, -4
 SP_SEQUENTIAL_ORDER, SP_APPLY_INPLACE = 1, 2
 
 EXPORTS = ("swiftprune_layer_stats", "swiftprune_score_select", "swiftprune_nm_select",
-           "swiftprune_apply", "swiftprune_count_pruned", "swiftprune_calibrate_la", "swiftprune_la_for_sparsity", "swiftprune_stats_workspace_bytes",
+           "swiftprune_apply", "swiftprune_count_pruned", "swiftprune_calibrate_la", "swiftprune_topk_select", "swiftprune_la_for_sparsity", "swiftprune_stats_workspace_bytes",
            "swiftprune_strerror", "swiftprune_version")
 
 
@@ -62,6 +62,8 @@ def load_library(path: str | None = None) -> C.CDLL:
     L.swiftprune_calibrate_la.argtypes = [vp, i64, i64, i64, i32, vp, f, f, f, f, f, f, vp,
                                           C.POINTER(C.c_float), C.POINTER(C.c_float), vp]
     L.swiftprune_calibrate_la.restype = i32
+    L.swiftprune_topk_select.argtypes = [vp, i64, i64, i64, i32, vp, vp, i64, vp, u32, vp]
+    L.swiftprune_topk_select.restype = i32
     L.swiftprune_la_for_sparsity.argtypes = [f, C.POINTER(C.c_float)]
     L.swiftprune_la_for_sparsity.restype = i32
     L.swiftprune_stats_workspace_bytes.argtypes = [i64, i64]
@@ -210,6 +212,18 @@ def swiftprune_calibrate_la(W, hr, target_sparsity: float, tolerance: float = 1e
     if code not in (SP_OK, SP_ERANGE):
         _check(code, "swiftprune_calibrate_la")
     return la.value, ach.value, code == SP_OK
+
+
+def swiftprune_topk_select(W, hr, keep_mask, k_per_row=None, k_uniform: int = 0, flags: int = 0, stream=None):
+    """Prune the k smallest scores of every row (k_per_row: int32 GPU tensor [out], or k_uniform)."""
+    import torch
+    ptr, out, n_in, ldw, dt = _matrix(W)
+    words = (n_in + 31) // 32
+    code = load_library().swiftprune_topk_select(
+        ptr, out, n_in, ldw, dt, _vec(hr, torch.float32, n_in, "hr"),
+        _vec(k_per_row, torch.int32, out, "k_per_row"), int(k_uniform),
+        _vec(keep_mask, torch.int32, out * words, "keep_mask"), int(flags), _stream(stream))
+    _check(code, "swiftprune_topk_select")
 
 
 def swiftprune_apply(W, keep_mask, stream=None):

@@ -160,6 +160,20 @@ int swiftprune_calibrate_la(const void* W, int64_t out, int64_t in, int64_t ldw,
     return status == 0 ? SP_OK : SP_ERANGE;
 }
 
+int swiftprune_topk_select(const void* W, int64_t out, int64_t in, int64_t ldw, sp_dtype dt,
+                           const float* hr, const int32_t* k_per_row, int64_t k_uniform,
+                           uint32_t* keep_mask, uint32_t flags, void* hip_stream) {
+    if (W == nullptr || hr == nullptr || keep_mask == nullptr) return SP_EINVAL;
+    if (out <= 0 || in <= 0 || ldw < in || !dtype_ok((int)dt)) return SP_EINVAL;
+    if (out > 0x7fffffff || in > (int64_t)1 << 30) return SP_EINVAL;
+    if (flags & ~SP_APPLY_INPLACE) return SP_EINVAL;
+    if (reinterpret_cast<uintptr_t>(W) % elem_size((int)dt) != 0) return SP_EINVAL;
+    const hipError_t e = sp::launch_topk_select(W, out, in, ldw, (int)dt, hr, k_per_row, k_uniform, keep_mask,
+                                                (flags & SP_APPLY_INPLACE) != 0,
+                                                static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? SP_OK : SP_EHIP;
+}
+
 int swiftprune_nm_select(const void* W, int64_t out, int64_t in, int64_t ldw, sp_dtype dt,
                          const float* hr, int n_keep, int m_group, uint32_t* keep_mask, float* scores,
                          uint32_t flags, void* hip_stream) {

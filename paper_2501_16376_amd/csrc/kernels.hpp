@@ -55,6 +55,11 @@ hipError_t run_calibrate_la(const void* W, int64_t out, int64_t in, int64_t ldw,
                             float la_lo, float la_hi, unsigned long long* counts_dev, float* la_out,
                             float* achieved_out, int* status, hipStream_t stream);
 
+// ---- exact per-row top-k comparator ----
+hipError_t launch_topk_select(const void* W, int64_t out, int64_t in, int64_t ldw, int dt,
+                              const float* hr, const int32_t* k_per_row, int64_t k_uniform,
+                              uint32_t* keep_mask, bool apply, hipStream_t stream);
+
 // ---- steps 2+3 structured, step 4 ----
 hipError_t launch_nm_select(const void* W, int64_t out, int64_t in, int64_t ldw, int dt, bool vec,
                             const float* hr, int n_keep, int m_group, uint32_t* keep_mask,

@@ -100,6 +100,24 @@ def test_argument_checks_do_not_launch(lib):
     assert nm(p, 8, 8, 8, 1, p, 0, 4, p, None, 0, None) == E
     assert nm(p, 8, 12, 12, 1, p, 4, 8, p, None, 0, None) == E        # in % m != 0
     assert nm(p, 8, 8, 8, 1, p, 2, 4, p, None, 1, None) == E          # strict-order flag not valid here
+    cp = lib.swiftprune_count_pruned
+    las = (C.c_float * 3)(0.5, 0.2, -0.2)
+    assert cp(p, 8, 8, 8, 1, p, 0.125, 0.125, las, 0, p, None) == E          # n_la < 1
+    assert cp(p, 8, 8, 8, 1, p, 0.125, 0.125, las, 17, p, None) == E         # n_la > 16
+    assert cp(p, 8, 8, 8, 1, p, 0.125, 0.125, None, 3, p, None) == E
+    assert cp(p, 8, 8, 8, 1, p, 0.125, 0.125, las, 3, p + 4, None) == E      # counts alignment
+    bad = (C.c_float * 2)(0.5, float("nan"))
+    assert cp(p, 8, 8, 8, 1, p, 0.125, 0.125, bad, 2, p, None) == E
+    cal = lib.swiftprune_calibrate_la
+    la_o, ach_o = C.c_float(), C.c_float()
+    assert cal(p, 8, 8, 8, 1, p, 0.125, 0.125, 0.0, 1e-3, -8.0, 8.0, p, C.byref(la_o), C.byref(ach_o), None) == E
+    assert cal(p, 8, 8, 8, 1, p, 0.125, 0.125, 0.3, 0.0, -8.0, 8.0, p, C.byref(la_o), C.byref(ach_o), None) == E
+    assert cal(p, 8, 8, 8, 1, p, 0.125, 0.125, 0.3, 1e-3, 2.0, 1.0, p, C.byref(la_o), C.byref(ach_o), None) == E
+    assert cal(p, 8, 8, 8, 1, p, 0.125, 0.125, 0.3, 1e-3, -8.0, 8.0, None, C.byref(la_o), C.byref(ach_o), None) == E
+    tk = lib.swiftprune_topk_select
+    assert tk(None, 8, 8, 8, 1, p, None, 4, p, 0, None) == E
+    assert tk(p, 8, 8, 8, 1, p, None, 4, None, 0, None) == E
+    assert tk(p, 8, 8, 8, 1, p, None, 4, p, 1, None) == E                    # strict-order flag not valid here
     ap = lib.swiftprune_apply
     assert ap(None, 8, 8, 8, 1, p, None) == E
     assert ap(p, 8, 8, 8, 1, None, None) == E
