@@ -173,7 +173,32 @@ int swiftprune_nm_select(const void *W, int64_t out, int64_t in, int64_t ldw, sp
 int swiftprune_apply(void *W, int64_t out, int64_t in, int64_t ldw, sp_dtype dt,
                      const uint32_t *keep_mask, void *hip_stream);
 
+/*
+ * Compact storage of an N:M-pruned matrix (Sec. 3.3 motivates N:M by formats that store only the kept
+ * values and their positions).  Open layout, not a vendor format:
+ *   values [out, in/m_group*n_keep] in W's dtype: values[r, g*N + j] = j-th kept entry (ascending
+ *          column) of group g of row r                                            (device, write)
+ *   meta   [out, swiftprune_nm_meta_words(in, n_keep, m_group)] uint32: the position 0..M-1 of that
+ *          entry inside its group as a field of b bits (b = 2 for M = 4, else 4); field number
+ *          g*N + j of the row, packed little-endian (field f = bits [f*b mod 32, +b) of word f*b/32)
+ * keep_mask should keep exactly n_keep entries per group (as swiftprune_nm_select produces): extra kept
+ * entries beyond the first n_keep of a group are dropped; a group with fewer is padded with +0 at
+ * position 0.  Patterns as for swiftprune_nm_select.
+ */
+int swiftprune_compact_nm(const void *W, int64_t out, int64_t in, int64_t ldw, sp_dtype dt,
+                          const uint32_t *keep_mask, int n_keep, int m_group, void *values,
+                          uint32_t *meta, void *hip_stream);
+
+/* Inverse of swiftprune_compact_nm: W_out[out, in] (pitch ldw_out) gets the stored values at their
+ * positions and +0 everywhere else. */
+int swiftprune_expand_nm(const void *values, const uint32_t *meta, int64_t out, int64_t in, sp_dtype dt,
+                         int n_keep, int m_group, void *W_out, int64_t ldw_out, void *hip_stream);
+
 /* ---- host helpers (no device work) ---- */
+
+/* uint32 words of meta per row for swiftprune_compact_nm (0 on an unsupported pattern). */
+size_t swiftprune_nm_meta_words(int64_t in, int n_keep, int m_group);
+
 
 /* la for a pruning ratio from the paper's table (0.9 -> -1.5, 0.8 -> -0.9, 0.7 -> -0.2,
  * 0.6 -> 0.2, 0.5 -> 0.5), piecewise linear between entries.  SP_EINVAL outside [0.5, 0.9]. */

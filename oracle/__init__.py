@@ -75,12 +75,14 @@ def _declare(L: C.CDLL) -> C.CDLL:
     L.oracle_ewma_select_literal_f32.argtypes = [_vp, _i64, _i64, _i64, _i32, _vp, _f, _f, _f, _f,
                                                  _vp, _vp, _vp]
     L.oracle_topk_select_f32.argtypes = [_vp, _i64, _i64, _i64, _i32, _vp, _vp, _i64, _vp]
+    L.oracle_compact_nm.argtypes = [_vp, _i64, _i64, _i64, _i32, _vp, _i32, _i32, _vp, _vp]
+    L.oracle_expand_nm.argtypes = [_vp, _vp, _i64, _i64, _i32, _i32, _i32, _vp]
     L.oracle_apply.argtypes = [_vp, _i64, _i64, _i64, _i32, _vp]
     for name in ("oracle_stats_accumulate", "oracle_stats_finalize", "oracle_channel_factor_f32",
                  "oracle_channel_factor_f64", "oracle_score_f32", "oracle_score_f64",
                  "oracle_ewma_row_f32", "oracle_ewma_row_f64", "oracle_ewma_select_f32",
                  "oracle_ewma_select_f64", "oracle_nm_select_f32", "oracle_nm_select_f64",
-                 "oracle_ewma_select_literal_f32", "oracle_topk_select_f32", "oracle_apply"):
+                 "oracle_ewma_select_literal_f32", "oracle_topk_select_f32", "oracle_compact_nm", "oracle_expand_nm", "oracle_apply"):
         getattr(L, name).restype = None
     return L
 
@@ -238,6 +240,33 @@ def topk_select(W: np.ndarray, hr: np.ndarray, k, L=None) -> np.ndarray:
         kp, ku = karr.ctypes.data, 0
     (L or lib()).oracle_topk_select_f32(ptr, out, n, ld, dt, hr.ctypes.data, kp, ku, mask.ctypes.data)
     return mask
+
+
+def nm_meta_words(n: int, n_keep: int, m_group: int) -> int:
+    bits = 2 if m_group == 4 else 4
+    return (n // m_group * n_keep * bits + 31) // 32
+
+
+def compact_nm(W: np.ndarray, keep_mask: np.ndarray, n_keep: int, m_group: int, L=None):
+    """(values [out, in/M*N] in W's dtype, meta uint32 [out, meta_words]) of an N:M-masked matrix."""
+    ptr, out, n, ld, dt = _mat(W)
+    keep_mask = np.ascontiguousarray(keep_mask, dtype=np.uint32)
+    values = np.empty((out, n // m_group * n_keep), dtype=W.dtype)
+    meta = np.empty((out, nm_meta_words(n, n_keep, m_group)), dtype=np.uint32)
+    (L or lib()).oracle_compact_nm(ptr, out, n, ld, dt, keep_mask.ctypes.data, n_keep, m_group,
+                                   values.ctypes.data, meta.ctypes.data)
+    return values, meta
+
+
+def expand_nm(values: np.ndarray, meta: np.ndarray, n: int, n_keep: int, m_group: int, L=None) -> np.ndarray:
+    """Dense [out, n] matrix from the compact form."""
+    values = np.ascontiguousarray(values)
+    meta = np.ascontiguousarray(meta, dtype=np.uint32)
+    out = values.shape[0]
+    W = np.empty((out, n), dtype=values.dtype)
+    (L or lib()).oracle_expand_nm(values.ctypes.data, meta.ctypes.data, out, n, _dtype_code(values),
+                                  n_keep, m_group, W.ctypes.data)
+    return W
 
 
 # ---------------------------------------------------------------- step 5

@@ -273,6 +273,80 @@ void oracle_topk_select_f32(const void *W, int64_t out, int64_t in, int64_t ldw,
 }
 
 /* ------------------------------------------------------------------ */
+/* Compact storage of an N:M-pruned matrix (Sec. 3.3 motivates N:M by   */
+/* hardware formats that store only the kept values plus their          */
+/* positions).  Open layout defined here, not a vendor format:          */
+/*   values[r, g*N + j]  = j-th kept entry (ascending column) of group g */
+/*   meta: the position (0..M-1) of that entry inside its group, as a    */
+/*         field of b bits (b = 2 for M = 4, else 4), field number       */
+/*         g*N + j of the row, packed little-endian into uint32 words;   */
+/*         meta_words = ceil(in/M * N * b / 32) per row.                 */
+/* A group with fewer than N kept entries is padded with +0 / position 0.*/
+/* ------------------------------------------------------------------ */
+
+static int nm_index_bits(int m_group) { return m_group == 4 ? 2 : 4; }
+
+void oracle_compact_nm(const void *W, int64_t out, int64_t in, int64_t ldw, int dt,
+                       const uint32_t *keep_mask, int n_keep, int m_group,
+                       void *values, uint32_t *meta)
+{
+    const int64_t words = (in + 31) / 32;
+    const int b = nm_index_bits(m_group);
+    const int64_t per_row = in / m_group * n_keep;
+    const int64_t meta_words = (per_row * b + 31) / 32;
+    for (int64_t r = 0; r < out; ++r) {
+        for (int64_t w = 0; w < meta_words; ++w) meta[r * meta_words + w] = 0u;
+        for (int64_t g = 0; g < in / m_group; ++g) {
+            int j = 0;
+            for (int i = 0; i < m_group && j < n_keep; ++i) {
+                int64_t q = g * m_group + i;
+                if (!((keep_mask[r * words + (q >> 5)] >> (q & 31)) & 1u)) continue;
+                int64_t f = g * n_keep + j;
+                if (dt == ORC_BF16)
+                    ((uint16_t *)values)[r * per_row + f] = ((const uint16_t *)W)[r * ldw + q];
+                else
+                    ((uint32_t *)values)[r * per_row + f] = ((const uint32_t *)W)[r * ldw + q];
+                meta[r * meta_words + (f * b >> 5)] |= (uint32_t)i << ((f * b) & 31);
+                ++j;
+            }
+            for (; j < n_keep; ++j) {
+                int64_t f = g * n_keep + j;
+                if (dt == ORC_BF16) ((uint16_t *)values)[r * per_row + f] = 0;
+                else ((uint32_t *)values)[r * per_row + f] = 0u;
+            }
+        }
+    }
+}
+
+/* Inverse: a dense [out, in] matrix (pitch in) with the stored values at their positions, +0 elsewhere. */
+void oracle_expand_nm(const void *values, const uint32_t *meta, int64_t out, int64_t in, int dt,
+                      int n_keep, int m_group, void *W_out)
+{
+    const int b = nm_index_bits(m_group);
+    const int64_t per_row = in / m_group * n_keep;
+    const int64_t meta_words = (per_row * b + 31) / 32;
+    for (int64_t r = 0; r < out; ++r) {
+        for (int64_t q = 0; q < in; ++q) {
+            if (dt == ORC_BF16) ((uint16_t *)W_out)[r * in + q] = 0;
+            else ((uint32_t *)W_out)[r * in + q] = 0u;
+        }
+        for (int64_t f = 0; f < per_row; ++f) {
+            uint32_t pos = (meta[r * meta_words + (f * b >> 5)] >> ((f * b) & 31)) & ((1u << b) - 1u);
+            int64_t q = f / n_keep * m_group + pos;
+            /* the output is already +0 everywhere: only non-zero bit patterns are placed, so a
+               padding entry (+0 at position 0) can never overwrite a stored value */
+            if (dt == ORC_BF16) {
+                uint16_t v = ((const uint16_t *)values)[r * per_row + f];
+                if (v != 0) ((uint16_t *)W_out)[r * in + q] = v;
+            } else {
+                uint32_t v = ((const uint32_t *)values)[r * per_row + f];
+                if (v != 0) ((uint32_t *)W_out)[r * in + q] = v;
+            }
+        }
+    }
+}
+
+/* ------------------------------------------------------------------ */
 /* Step 5: apply (Algorithm 1: w_i = 0 for pruned entries, c_i = w_i).  */
 /* ------------------------------------------------------------------ */
 

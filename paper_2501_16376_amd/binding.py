@@ -20,7 +20,7 @@ SP_OK, SP_EINVAL, SP_ENOSPC, SP_EHIP, SP_ERANGE = 0, -1, -2, -3, -4
 SP_SEQUENTIAL_ORDER, SP_APPLY_INPLACE = 1, 2
 
 EXPORTS = ("swiftprune_layer_stats", "swiftprune_score_select", "swiftprune_nm_select",
-           "swiftprune_apply", "swiftprune_count_pruned", "swiftprune_calibrate_la", "swiftprune_topk_select", "swiftprune_la_for_sparsity", "swiftprune_stats_workspace_bytes",
+           "swiftprune_apply", "swiftprune_count_pruned", "swiftprune_calibrate_la", "swiftprune_topk_select", "swiftprune_compact_nm", "swiftprune_expand_nm", "swiftprune_nm_meta_words", "swiftprune_la_for_sparsity", "swiftprune_stats_workspace_bytes",
            "swiftprune_strerror", "swiftprune_version")
 
 
@@ -64,6 +64,12 @@ def load_library(path: str | None = None) -> C.CDLL:
     L.swiftprune_calibrate_la.restype = i32
     L.swiftprune_topk_select.argtypes = [vp, i64, i64, i64, i32, vp, vp, i64, vp, u32, vp]
     L.swiftprune_topk_select.restype = i32
+    L.swiftprune_compact_nm.argtypes = [vp, i64, i64, i64, i32, vp, i32, i32, vp, vp, vp]
+    L.swiftprune_compact_nm.restype = i32
+    L.swiftprune_expand_nm.argtypes = [vp, vp, i64, i64, i32, i32, i32, vp, i64, vp]
+    L.swiftprune_expand_nm.restype = i32
+    L.swiftprune_nm_meta_words.argtypes = [i64, i32, i32]
+    L.swiftprune_nm_meta_words.restype = C.c_size_t
     L.swiftprune_la_for_sparsity.argtypes = [f, C.POINTER(C.c_float)]
     L.swiftprune_la_for_sparsity.restype = i32
     L.swiftprune_stats_workspace_bytes.argtypes = [i64, i64]
@@ -224,6 +230,40 @@ def swiftprune_topk_select(W, hr, keep_mask, k_per_row=None, k_uniform: int = 0,
         _vec(k_per_row, torch.int32, out, "k_per_row"), int(k_uniform),
         _vec(keep_mask, torch.int32, out * words, "keep_mask"), int(flags), _stream(stream))
     _check(code, "swiftprune_topk_select")
+
+
+def swiftprune_nm_meta_words(n_in: int, n_keep: int, m_group: int) -> int:
+    return int(load_library().swiftprune_nm_meta_words(int(n_in), int(n_keep), int(m_group)))
+
+
+def swiftprune_compact_nm(W, keep_mask, n_keep: int, m_group: int, values, meta, stream=None):
+    """values [out, in/M*N] (W's dtype) and meta int32 [out, meta_words] from an N:M-masked W."""
+    import torch
+    ptr, out, n_in, ldw, dt = _matrix(W)
+    words = (n_in + 31) // 32
+    mw = swiftprune_nm_meta_words(n_in, n_keep, m_group)
+    if mw == 0:
+        raise SwiftPruneError(SP_EINVAL, "swiftprune_compact_nm")
+    code = load_library().swiftprune_compact_nm(
+        ptr, out, n_in, ldw, dt, _vec(keep_mask, torch.int32, out * words, "keep_mask"), int(n_keep),
+        int(m_group), _vec(values, W.dtype, out * (n_in // m_group * n_keep), "values"),
+        _vec(meta, torch.int32, out * mw, "meta"), _stream(stream))
+    _check(code, "swiftprune_compact_nm")
+
+
+def swiftprune_expand_nm(values, meta, n_in: int, n_keep: int, m_group: int, W_out, stream=None):
+    import torch
+    ptr, out, n2, ldw, dt = _matrix(W_out)
+    if n2 != n_in:
+        raise ValueError("W_out must have n_in columns")
+    mw = swiftprune_nm_meta_words(n_in, n_keep, m_group)
+    if mw == 0:
+        raise SwiftPruneError(SP_EINVAL, "swiftprune_expand_nm")
+    code = load_library().swiftprune_expand_nm(
+        _vec(values, W_out.dtype, out * (n_in // m_group * n_keep), "values"),
+        _vec(meta, torch.int32, out * mw, "meta"), out, n_in, dt, int(n_keep), int(m_group), ptr, ldw,
+        _stream(stream))
+    _check(code, "swiftprune_expand_nm")
 
 
 def swiftprune_apply(W, keep_mask, stream=None):

@@ -190,6 +190,43 @@ int swiftprune_nm_select(const void* W, int64_t out, int64_t in, int64_t ldw, sp
     return e == hipSuccess ? SP_OK : SP_EHIP;
 }
 
+static bool nm_pattern_ok(int64_t in, int n_keep, int m_group) {
+    if (m_group != 4 && m_group != 8 && m_group != 16) return false;
+    return n_keep > 0 && n_keep < m_group && in % m_group == 0;
+}
+
+size_t swiftprune_nm_meta_words(int64_t in, int n_keep, int m_group) {
+    if (in <= 0 || !nm_pattern_ok(in, n_keep, m_group)) return 0;
+    return (size_t)sp::nm_meta_words(in, n_keep, m_group);
+}
+
+int swiftprune_compact_nm(const void* W, int64_t out, int64_t in, int64_t ldw, sp_dtype dt,
+                          const uint32_t* keep_mask, int n_keep, int m_group, void* values,
+                          uint32_t* meta, void* hip_stream) {
+    if (W == nullptr || keep_mask == nullptr || values == nullptr || meta == nullptr) return SP_EINVAL;
+    if (out <= 0 || in <= 0 || ldw < in || !dtype_ok((int)dt) || out > 65535 * (int64_t)65535) return SP_EINVAL;
+    if (!nm_pattern_ok(in, n_keep, m_group)) return SP_EINVAL;
+    if (reinterpret_cast<uintptr_t>(W) % elem_size((int)dt) != 0 ||
+        reinterpret_cast<uintptr_t>(values) % elem_size((int)dt) != 0)
+        return SP_EINVAL;
+    const hipError_t e = sp::launch_compact_nm(W, out, in, ldw, (int)dt, keep_mask, n_keep, m_group, values,
+                                               meta, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? SP_OK : SP_EHIP;
+}
+
+int swiftprune_expand_nm(const void* values, const uint32_t* meta, int64_t out, int64_t in, sp_dtype dt,
+                         int n_keep, int m_group, void* W_out, int64_t ldw_out, void* hip_stream) {
+    if (values == nullptr || meta == nullptr || W_out == nullptr) return SP_EINVAL;
+    if (out <= 0 || in <= 0 || ldw_out < in || !dtype_ok((int)dt)) return SP_EINVAL;
+    if (!nm_pattern_ok(in, n_keep, m_group)) return SP_EINVAL;
+    if (reinterpret_cast<uintptr_t>(W_out) % elem_size((int)dt) != 0 ||
+        reinterpret_cast<uintptr_t>(values) % elem_size((int)dt) != 0)
+        return SP_EINVAL;
+    const hipError_t e = sp::launch_expand_nm(values, meta, out, in, (int)dt, n_keep, m_group, W_out, ldw_out,
+                                              static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? SP_OK : SP_EHIP;
+}
+
 int swiftprune_apply(void* W, int64_t out, int64_t in, int64_t ldw, sp_dtype dt,
                      const uint32_t* keep_mask, void* hip_stream) {
     if (W == nullptr || keep_mask == nullptr) return SP_EINVAL;

@@ -60,6 +60,14 @@ hipError_t launch_topk_select(const void* W, int64_t out, int64_t in, int64_t ld
                               const float* hr, const int32_t* k_per_row, int64_t k_uniform,
                               uint32_t* keep_mask, bool apply, hipStream_t stream);
 
+// ---- compact N:M storage ----
+int64_t nm_meta_words(int64_t in, int n_keep, int m_group);
+hipError_t launch_compact_nm(const void* W, int64_t out, int64_t in, int64_t ldw, int dt,
+                             const uint32_t* keep_mask, int n_keep, int m_group, void* values,
+                             uint32_t* meta, hipStream_t stream);
+hipError_t launch_expand_nm(const void* values, const uint32_t* meta, int64_t out, int64_t in, int dt,
+                            int n_keep, int m_group, void* W_out, int64_t ldw, hipStream_t stream);
+
 // ---- steps 2+3 structured, step 4 ----
 hipError_t launch_nm_select(const void* W, int64_t out, int64_t in, int64_t ldw, int dt, bool vec,
                             const float* hr, int n_keep, int m_group, uint32_t* keep_mask,

@@ -434,7 +434,39 @@ def pin_topk_is_library_sort(orc, L=None):
     assert np.all((~keep4).sum(1) == 40)
 
 
-ALL_PINS = [pin_topk_is_library_sort, pin_worked_rows, pin_closed_form, pin_constant_row, pin_first_two_elements,
+def pin_compact_nm(orc, L=None):
+    """Compact N:M storage: a hand-made example, and expand(compact(W)) == apply(W, mask) for masks from
+    the N:M selection (2:4, 4:8, 1:4, 6:8, 8:16); values are the kept entries in column order."""
+    from paper_2501_16376_amd import synth
+    # one row, two groups of four: keep columns {1,3} and {4,6}
+    W = np.array([[10, 11, 12, 13, 14, 15, 16, 17]], dtype=np.float32)
+    mask = np.array([[0b01011010]], dtype=np.uint32)
+    vals, meta = orc.compact_nm(W, mask, 2, 4, L=L)
+    assert vals.tolist() == [[11, 13, 14, 16]]
+    assert meta.tolist() == [[1 | 3 << 2 | 0 << 4 | 2 << 6]]       # positions 1,3,0,2 in 2-bit fields
+    assert np.array_equal(orc.expand_nm(vals, meta, 8, 2, 4, L=L), [[0, 11, 0, 13, 14, 0, 16, 0]])
+    # 4:8 uses 4-bit fields: keep {0,2,5,7}
+    mask8 = np.array([[0b10100101]], dtype=np.uint32)
+    vals8, meta8 = orc.compact_nm(W, mask8, 4, 8, L=L)
+    assert vals8.tolist() == [[10, 12, 15, 17]] and meta8.tolist() == [[0 | 2 << 4 | 5 << 8 | 7 << 12]]
+    Wb, Xb = synth.layer_inputs(12, 192, 64, seed=17, dtype="bf16", n_outlier=2)
+    _, _, hr = orc.layer_stats(Xb, L=L)
+    for nk, m in ((2, 4), (4, 8), (1, 4), (6, 8), (8, 16)):
+        nm, _ = orc.nm_select(Wb, hr, nk, m, L=L)
+        vals, meta = orc.compact_nm(Wb, nm, nk, m, L=L)
+        assert vals.shape == (12, 192 // m * nk) and meta.shape == (12, orc.nm_meta_words(192, nk, m))
+        keep = orc.unpack_mask(nm, 192)
+        assert np.array_equal(vals, Wb[keep].reshape(12, -1))
+        dense = orc.expand_nm(vals, meta, 192, nk, m, L=L)
+        assert np.array_equal(dense, orc.apply(Wb.copy(), nm, L=L)), (nk, m)
+    # a group with fewer kept entries than N is padded with +0 and still round-trips
+    sparse_mask = np.array([[0b00000010]], dtype=np.uint32)         # group 0 keeps only column 1, group 1 nothing
+    vals, meta = orc.compact_nm(W, sparse_mask, 2, 4, L=L)
+    assert vals.tolist() == [[11, 0, 0, 0]]
+    assert np.array_equal(orc.expand_nm(vals, meta, 8, 2, 4, L=L), [[0, 11, 0, 0, 0, 0, 0, 0]])
+
+
+ALL_PINS = [pin_topk_is_library_sort, pin_compact_nm, pin_worked_rows, pin_closed_form, pin_constant_row, pin_first_two_elements,
             pin_monotone_in_la, pin_step_response, pin_stats_library_sum, pin_inverse_identity,
             pin_float_factor_matches_double, pin_select_metamorphic,
             pin_uniform_energy_reduces_to_magnitude, pin_nm_invariants,

@@ -118,6 +118,15 @@ def test_argument_checks_do_not_launch(lib):
     assert tk(None, 8, 8, 8, 1, p, None, 4, p, 0, None) == E
     assert tk(p, 8, 8, 8, 1, p, None, 4, None, 0, None) == E
     assert tk(p, 8, 8, 8, 1, p, None, 4, p, 1, None) == E                    # strict-order flag not valid here
+    cn = lib.swiftprune_compact_nm
+    assert cn(p, 8, 8, 8, 1, p, 2, 4, None, p, None) == E
+    assert cn(p, 8, 8, 8, 1, p, 2, 5, p, p, None) == E
+    assert cn(p, 8, 12, 12, 1, p, 4, 8, p, p, None) == E
+    ex = lib.swiftprune_expand_nm
+    assert ex(p, p, 8, 8, 1, 2, 4, p, 4, None) == E                          # pitch < columns
+    assert ex(p, None, 8, 8, 1, 2, 4, p, 8, None) == E
+    assert lib.swiftprune_nm_meta_words(4096, 2, 4) == 128 and lib.swiftprune_nm_meta_words(4096, 4, 8) == 256
+    assert lib.swiftprune_nm_meta_words(4096, 2, 5) == 0 and lib.swiftprune_nm_meta_words(10, 2, 4) == 0
     ap = lib.swiftprune_apply
     assert ap(None, 8, 8, 8, 1, p, None) == E
     assert ap(p, 8, 8, 8, 1, None, None) == E

@@ -139,3 +139,41 @@ def test_ewma_vs_sort_overlap_at_scale(orc, gpu):
         say(f"[report] la={la:+.1f}: achieved sparsity {k_tot / (out * n):.4f}, "
             f"EWMA-vs-sort overlap {overlap:.4f}")
         assert overlap > 0.85
+
+
+@pytest.mark.parametrize("out,n,dtype", [(40, 4096, "bf16"), (7, 1000, "bf16"), (5, 2048, "f32")])
+def test_compact_and_expand_nm(orc, gpu, out, n, dtype):
+    """Compact values/meta and the expanded matrix equal the oracle's, bit for bit."""
+    import torch
+    from paper_2501_16376_amd import binding as b, synth
+    from gpu_util import to_device, mask_to_host
+    Wh, hr, W, hr_dev = _inputs(orc, gpu, out, n, 128, seed=3 * out + n, dtype=dtype)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    for nk, m in ((2, 4), (4, 8), (1, 4), (6, 8), (8, 16)):
+        if n % m:
+            continue
+        say(f"[case] compact {nk}:{m} out={out} in={n} {dtype}")
+        mask = torch.empty((out, (n + 31) // 32), dtype=torch.int32, device=gpu)
+        b.swiftprune_nm_select(W, hr_dev, nk, m, mask)
+        mw = b.swiftprune_nm_meta_words(n, nk, m)
+        assert mw == orc.nm_meta_words(n, nk, m)
+        vals = torch.full((out, n // m * nk), 7, dtype=tdt, device=gpu)
+        meta = torch.full((out, mw), -1, dtype=torch.int32, device=gpu)
+        b.swiftprune_compact_nm(W, mask, nk, m, vals, meta)
+        dense = torch.full((out, n + 8), 3, dtype=tdt, device=gpu)[:, :n]
+        b.swiftprune_expand_nm(vals, meta, n, nk, m, dense)
+        torch.cuda.synchronize()
+        v_o, m_o = orc.compact_nm(Wh, mask_to_host(mask), nk, m)
+        assert np.array_equal(synth.torch_to_host_bits(vals), v_o)
+        assert np.array_equal(mask_to_host(meta), m_o)
+        assert np.array_equal(synth.torch_to_host_bits(dense), orc.expand_nm(v_o, m_o, n, nk, m))
+        assert np.array_equal(synth.torch_to_host_bits(dense), orc.apply(Wh.copy(), mask_to_host(mask)))
+    # a mask that is not N:M (EWMA mask): extra kept entries dropped, missing ones padded - same as the oracle
+    mask = torch.empty((out, (n + 31) // 32), dtype=torch.int32, device=gpu)
+    b.swiftprune_score_select(W, hr_dev, mask, la=0.5)
+    vals = torch.empty((out, n // 2), dtype=tdt, device=gpu)
+    meta = torch.empty((out, b.swiftprune_nm_meta_words(n, 2, 4)), dtype=torch.int32, device=gpu)
+    b.swiftprune_compact_nm(W, mask, 2, 4, vals, meta)
+    torch.cuda.synchronize()
+    v_o, m_o = orc.compact_nm(Wh, mask_to_host(mask), 2, 4)
+    assert np.array_equal(synth.torch_to_host_bits(vals), v_o) and np.array_equal(mask_to_host(meta), m_o)
