@@ -260,8 +260,7 @@ def committed_traffic():
             k, v = line.split("=", 1)
             kv[k.strip()] = v.strip()
     h = hashlib.sha256()
-    for f in ("stats.hip", "common.hpp"):
-        h.update(open(os.path.join(ROOT, "paper_2501_16376_amd", "csrc", f), "rb").read())
+    h.update(open(os.path.join(ROOT, "paper_2501_16376_amd", "csrc", "stats.hip"), "rb").read())
     if kv.get("kernel_source_sha256") != h.hexdigest():
         return None
     try:

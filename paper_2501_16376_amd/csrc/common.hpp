@@ -82,6 +82,14 @@ struct Chunk8<kBF16> {
             raw[j] &= m;
         }
     }
+    // zero the elements whose flag is set (two selects per 32-bit pair)
+    __device__ __forceinline__ void apply_flags(const bool* prune) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t lo_gone = prune[2 * j] ? (raw[j] & 0xffff0000u) : raw[j];
+            raw[j] = prune[2 * j + 1] ? (lo_gone & 0x0000ffffu) : lo_gone;
+        }
+    }
     __device__ __forceinline__ void store_vec(void* base, int64_t elem_off) const {
         *reinterpret_cast<uint4*>(static_cast<uint16_t*>(base) + elem_off) =
             make_uint4(raw[0], raw[1], raw[2], raw[3]);
@@ -117,6 +125,10 @@ struct Chunk8<kF32> {
 #pragma unroll
         for (int k = 0; k < 8; ++k)
             if (!((keep_byte >> k) & 1u)) raw[k] = 0u;
+    }
+    __device__ __forceinline__ void apply_flags(const bool* prune) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) raw[k] = prune[k] ? 0u : raw[k];
     }
     __device__ __forceinline__ void store_vec(void* base, int64_t elem_off) const {
         uint4* p = reinterpret_cast<uint4*>(static_cast<float*>(base) + elem_off);

@@ -31,6 +31,8 @@ hipError_t launch_layer_stats(const void* X, int64_t tokens, int64_t in, int64_t
 // ---- steps 2+3: EWMA selection ----
 struct EwmaConsts {
     float alpha, beta, la;
+    float inv_alpha;    // 1 / alpha
+    float thr_scale;    // (1-alpha) * la * beta: prune iff alpha*x_k - L_k > thr_scale * y_{k-1}
     float A_pow[9];     // (1-alpha)^k, k = 0..8
     float B_pow[9];     // (1-beta)^k
     double A8_sq[7];    // ((1-alpha)^8)^(2^i), i = 0..6
