@@ -33,7 +33,10 @@ def parse():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--blocks", type=int, default=32, help="decoder blocks in the stack (32 = the 8B shape)")
-    ap.add_argument("--model", default="llama3-8b", choices=["llama3-8b", "llama2-7b"])
+    ap.add_argument("--model", default="llama3-8b", choices=["llama3-8b", "llama2-7b", "llama2-70b"],
+                    help="block shape; llama2-70b has 80 blocks of 1.7 GB: pass --blocks <= 32 so that the "
+                         "weights, their pristine copy and the activations fit in HBM")
+    ap.add_argument("--la", type=float, default=0.5, help="threshold multiplier of the unstructured mode")
     ap.add_argument("--mode", default="unstructured", choices=["unstructured", "2:4", "4:8"])
     ap.add_argument("--tokens", type=int, default=128 * 2048)
     ap.add_argument("--shared-stats", action="store_true",
@@ -67,10 +70,11 @@ def main():
     torch.cuda.set_device(dev)
     sp.load_library()
 
-    block = synth.LLAMA3_8B_BLOCK if args.model == "llama3-8b" else synth.LLAMA2_7B_BLOCK
+    block = {"llama3-8b": synth.LLAMA3_8B_BLOCK, "llama2-7b": synth.LLAMA2_7B_BLOCK,
+             "llama2-70b": synth.LLAMA2_70B_BLOCK}[args.model]
     T = args.tokens
     nm = None if args.mode == "unstructured" else tuple(int(x) for x in args.mode.split(":"))
-    la = 0.5
+    la = args.la
 
     # ---- resident data: activations per distinct layer input, weights per (block, layer)
     t_setup = time.time()
@@ -225,7 +229,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{args.model}-shaped stack, {args.blocks} blocks x 7 linear layers, bf16 W, "
                                f"{T} calibration tokens per layer, "
-                               + ("50% unstructured (la=0.5)" if nm is None else f"{args.mode} structured"),
+                               + (f"unstructured (la={la:g})" if nm is None else f"{args.mode} structured"),
                    "storage": "bf16", "tokens": T, "blocks": args.blocks, "mode": args.mode,
                    "stats_calls_per_block": 4 if args.shared_stats else 7, "streams": args.streams,
                    "weights": n_weights},
