@@ -230,6 +230,62 @@ def test_stats_chunked_and_deterministic(orc, gpu):
     assert np.allclose(chunked[2], hr_o, rtol=1e-5, atol=0)
 
 
+@pytest.mark.parametrize("tokens,n,dtype", [(37, 40000, "bf16"), (5, 70001, "f32"), (4099, 8, "bf16"),
+                                             (100000, 64, "f32"), (9, 2049, "bf16")])
+def test_stats_wide_and_tall(orc, gpu, tokens, n, dtype):
+    """Statistics on shapes far from the Llama ones: many strips with one token range, a single narrow
+    strip with many ranges, odd widths on the element-wise path."""
+    from paper_2501_16376_amd import synth
+    from gpu_util import to_device
+    say(f"[case] stats tokens={tokens} in={n} {dtype}")
+    _, Xh = synth.layer_inputs(1, n, tokens, seed=tokens + n, dtype=dtype)
+    xsq_o, S_o, hr_o = orc.layer_stats(Xh)
+    xsq_g, S_g, hr_g = _stats_gpu(to_device(Xh, gpu), n)
+    assert np.allclose(xsq_g, xsq_o, rtol=1e-5, atol=0)
+    assert abs(S_g - S_o) <= 1e-5 * S_o
+    assert np.allclose(hr_g, hr_o, rtol=1e-5, atol=0)
+
+
+def test_graph_capture_replays(orc, gpu):
+    """The whole layer path (statistics, selection + apply) records into a HIP graph - the library
+    allocates nothing and never synchronises - and every replay reproduces the eager result, with eager
+    work and synchronisations between the replays."""
+    import torch
+    from paper_2501_16376_amd import binding as b, synth
+    from gpu_util import mask_to_host
+    out, n, tokens = 512, 2048, 4096
+    X = synth.device_activations(tokens, n, seed=21, device=gpu)
+    W0 = synth.device_weights(out, n, seed=22, device=gpu)
+    bufs = b.LayerBuffers(out, n, tokens, gpu)
+    # eager reference
+    W = W0.clone()
+    b.prune_layer(W, X, bufs, la=0.5)
+    torch.cuda.synchronize()
+    ref_W, ref_mask = synth.torch_to_host_bits(W), mask_to_host(bufs.keep_mask).copy()
+    ref_hr = bufs.hr.cpu().numpy().copy()
+    # capture
+    Wg = W0.clone()
+    side = torch.cuda.Stream(device=gpu)
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        b.prune_layer(Wg, X, bufs, la=0.5)                 # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        b.prune_layer(Wg, X, bufs, la=0.5)
+    for rep in range(3):
+        Wg.copy_(W0)                                       # eager work between replays
+        bufs.keep_mask.zero_()
+        bufs.hr.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(bufs.hr.cpu().numpy(), ref_hr), rep
+        assert np.array_equal(mask_to_host(bufs.keep_mask), ref_mask), rep
+        assert np.array_equal(synth.torch_to_host_bits(Wg), ref_W), rep
+
+
 def test_degenerate_statistics(orc, gpu):
     """All-zero activations -> S = 0, factor 1/2; one channel holding all the energy -> clamped denominator."""
     import torch
