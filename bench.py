@@ -31,7 +31,7 @@ def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--blocks", type=int, default=32, help="decoder blocks in the stack (32 = the 8B shape)")
     ap.add_argument("--model", default="llama3-8b", choices=["llama3-8b", "llama2-7b", "llama2-70b"],
                     help="block shape; llama2-70b has 80 blocks of 1.7 GB: pass --blocks <= 32 so that the "
@@ -174,10 +174,12 @@ def main():
         for W, P in zip(weights, pristine):
             W.copy_(P)
 
-    for _ in range(args.warmup):
+    for _ in range(args.warmup):          # identical to a timed step, instrumentation included
         restore()
-        step(False)
+        torch.cuda.synchronize()
+        step(not args.no_kernel_events)
     torch.cuda.synchronize()
+    ev_pairs.clear()
 
     step_events = []
     t_wall0 = time.time()
@@ -235,6 +237,7 @@ def main():
                    "weights": n_weights},
         "seconds_per_model": round(ms_per_step * 1e-3, 5),
         "step_ms_min_max": [round(min(step_ms), 3), round(max(step_ms), 3)],
+        "step_ms": [round(x, 2) for x in step_ms],
         "algorithmic_bytes_per_step": int(algo_bytes),
         "hbm_frac_whole_step": round(algo_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "achieved_sparsity_last_layer": pruned_frac,

@@ -15,8 +15,9 @@ struct StatsPlan {
     int64_t units;           // ceil(in / epu)
     int strip_units;         // units per column strip (<= 256, one per lane of a workgroup)
     int nstrips;             // column strips
-    int splits;              // token ranges per strip
-    int64_t rows_per_split;  // tokens handled by one workgroup
+    int splits;              // workgroups per strip; row batches are dealt to them round-robin
+    int unroll;              // rows per batch (4 or 8)
+    int64_t rows_per_split;  // upper bound of the tokens one workgroup sees
     int combine_groups;      // workgroups of the combine kernel (64 columns each)
     size_t partial_floats;   // splits * units * epu
 };

@@ -5,12 +5,14 @@
 // X[tokens, in] is streamed exactly once with non-temporal 16-byte loads.  The
 // columns are cut into strips of at most 256 sixteen-byte units (one unit per
 // lane of a 256-thread workgroup: 2048 bf16 or 1024 fp32 columns, contiguous in
-// every row) and the tokens into ranges; strips x ranges is chosen to be about
-// one workgroup per compute unit, which measured fastest on MI355X (more
-// resident workgroups lower the achieved HBM rate).  Every lane keeps fp32
-// running sums for the columns of its unit, eight rows in flight, four
-// independent accumulator sets so no serial fp32 chain exceeds a quarter of the
-// range.  Each workgroup writes one partial row segment and the fp64 sum of it;
+// every row) and the tokens into batches of 4 or 8 consecutive rows that are
+// dealt round-robin to `splits` workgroups per strip, so that at any moment the
+// whole device reads one moving window of a few MB (measured 1-7 % faster than
+// giving every workgroup its own contiguous token range); strips x splits is
+// about one workgroup per compute unit (more resident workgroups lower the
+// achieved HBM rate).  Every lane keeps fp32 running sums for the columns of
+// its unit, a batch of rows in flight, four independent accumulator sets so no
+// serial fp32 chain exceeds a quarter of the rows a workgroup sees.  Each workgroup writes one partial row segment and the fp64 sum of it;
 // a second small kernel adds the partial rows of every column in fp64 in a fixed
 // order (LDS-staged), adds the per-workgroup sums in index order to get S (every
 // workgroup redoes that small sum, so none waits for another) and writes the
@@ -21,9 +23,8 @@
 namespace sp {
 
 constexpr int kStatsThreads = 256;       // one wide strip per workgroup, 4 wavefronts
-constexpr int kStatsUnroll = 8;          // rows (independent 16-byte loads) in flight per lane
 constexpr int kStatsSets = 4;            // independent accumulator sets per column
-constexpr int kStatsTargetGroups = 256;  // one workgroup per compute unit
+constexpr int kStatsComputeUnits = 256;   // MI355X
 constexpr int kCombineThreads = 256;     // 64 columns x 4 groups of partial rows
 constexpr int kCombineGroups = kCombineThreads / 64;
 
@@ -94,22 +95,22 @@ __device__ __forceinline__ double block_sum_256(double v, double* lds4) {
     return t;
 }
 
-// grid = (nstrips, splits), block = 256.
-// partials[split * in_pad + u*EPU + k] = sum over the workgroup's token range of X[t, u*EPU + k]^2
+// grid = (nstrips, splits), block = 256.  Workgroup (strip, split) takes the row batches
+// b = split, split + splits, ... (batch b = rows [b*UNROLL, (b+1)*UNROLL)).
+// partials[split * in_pad + u*EPU + k] = sum over those rows of X[t, u*EPU + k]^2
 // for the units u of its strip (in_pad = units * EPU);
 // group_sums[strip * splits + split] = fp64 sum of that partial row segment (its share of S).
-template <int DT, int EPU>
+template <int DT, int EPU, int UNROLL>
 __global__ __launch_bounds__(kStatsThreads) __attribute__((amdgpu_waves_per_eu(1, 2))) void stats_partial_kernel(
     const void* __restrict__ X, int64_t tokens, int64_t units, int strip_units, int64_t ldx,
-    int64_t rows_per_split, float* __restrict__ partials, double* __restrict__ group_sums) {
+    float* __restrict__ partials, double* __restrict__ group_sums) {
     __shared__ double lds4[4];
     const int strip = blockIdx.x;
     const int split = blockIdx.y;
+    const int64_t splits = gridDim.y;
     const int64_t u = (int64_t)strip * strip_units + threadIdx.x;
     const bool active = (int)threadIdx.x < strip_units && u < units;
     const int64_t col = u * EPU;
-    const int64_t r_begin = (int64_t)split * rows_per_split;
-    const int64_t r_end = min(tokens, r_begin + rows_per_split);
 
     float acc[kStatsSets][EPU];
 #pragma unroll
@@ -119,15 +120,16 @@ __global__ __launch_bounds__(kStatsThreads) __attribute__((amdgpu_waves_per_eu(1
 
     double lane_total = 0.0;
     if (active) {
-        int64_t r = r_begin;
-        for (; r + kStatsUnroll <= r_end; r += kStatsUnroll) {
-            XUnit<DT, EPU> v[kStatsUnroll];
+        int64_t r = (int64_t)split * UNROLL;
+        const int64_t step = splits * UNROLL;
+        for (; r + UNROLL <= tokens; r += step) {
+            XUnit<DT, EPU> v[UNROLL];
 #pragma unroll
-            for (int j = 0; j < kStatsUnroll; ++j) v[j].load(X, (r + j) * ldx + col);
+            for (int j = 0; j < UNROLL; ++j) v[j].load(X, (r + j) * ldx + col);
 #pragma unroll
-            for (int j = 0; j < kStatsUnroll; ++j) v[j].sq_add(acc[j % kStatsSets]);
+            for (int j = 0; j < UNROLL; ++j) v[j].sq_add(acc[j % kStatsSets]);
         }
-        for (; r < r_end; ++r) {
+        for (; r < tokens; ++r) {  // the one batch that is cut short by the end of X, if it is ours
             XUnit<DT, EPU> v;
             v.load(X, r * ldx + col);
             v.sq_add(acc[0]);
@@ -136,7 +138,6 @@ __global__ __launch_bounds__(kStatsThreads) __attribute__((amdgpu_waves_per_eu(1
 #pragma unroll
         for (int k = 0; k < EPU; ++k) {
             const float t = (acc[0][k] + acc[1][k]) + (acc[2][k] + acc[3][k]);
-            // element-wise path: the last unit may hold columns past `in`; they were never loaded
             p[k] = t;
             lane_total += (double)t;
         }
@@ -230,13 +231,19 @@ StatsPlan make_stats_plan(int64_t tokens, int64_t in, int dt, bool vec) {
     if (su > kStatsThreads) su = kStatsThreads;
     p.strip_units = (int)su;
     p.nstrips = (int)ceil_div(p.units, su);
-    // about one workgroup per compute unit, and no range shorter than one batch of rows
-    int64_t splits = kStatsTargetGroups / p.nstrips;
-    const int64_t max_splits = ceil_div(tokens, kStatsUnroll);
-    if (splits > max_splits) splits = max_splits;
+    // Rows in flight per lane and workgroups per compute unit, from sweeps over the Llama widths
+    // (4096, 8192, 11008, 14336, 28672) on MI355X: a power-of-two number of strips maps every strip
+    // to a fixed subset of the 8 XCDs and does best with 4 rows in flight and 1.5 workgroups per
+    // compute unit; otherwise 8 rows and 1 workgroup.
+    const bool pow2_strips = (p.nstrips & (p.nstrips - 1)) == 0;
+    p.unroll = pow2_strips ? 4 : 8;
+    const int64_t target = pow2_strips ? kStatsComputeUnits * 3 / 2 : kStatsComputeUnits;
+    int64_t splits = target / p.nstrips;
+    const int64_t batches = ceil_div(tokens, p.unroll);
+    if (splits > batches) splits = batches;
     if (splits < 1) splits = 1;
-    p.rows_per_split = ceil_div(tokens, splits);
-    p.splits = (int)ceil_div(tokens, p.rows_per_split);  // drop ranges that would be empty
+    p.splits = (int)splits;
+    p.rows_per_split = ceil_div(batches, splits) * p.unroll;  // upper bound, informational
     p.combine_groups = (int)ceil_div(in, 64);
     p.partial_floats = (size_t)p.splits * (size_t)(p.units * p.epu);
     return p;
@@ -254,8 +261,12 @@ template <int DT, int EPU>
 static hipError_t launch_partial(const void* X, int64_t tokens, int64_t ldx, const StatsPlan& p,
                                  float* partials, double* group_sums, hipStream_t stream) {
     dim3 grid((unsigned)p.nstrips, (unsigned)p.splits);
-    hipLaunchKernelGGL((stats_partial_kernel<DT, EPU>), grid, dim3(kStatsThreads), 0, stream, X, tokens,
-                       p.units, p.strip_units, ldx, p.rows_per_split, partials, group_sums);
+    if (p.unroll == 4)
+        hipLaunchKernelGGL((stats_partial_kernel<DT, EPU, 4>), grid, dim3(kStatsThreads), 0, stream, X, tokens,
+                           p.units, p.strip_units, ldx, partials, group_sums);
+    else
+        hipLaunchKernelGGL((stats_partial_kernel<DT, EPU, 8>), grid, dim3(kStatsThreads), 0, stream, X, tokens,
+                           p.units, p.strip_units, ldx, partials, group_sums);
     return hipGetLastError();
 }
 
