@@ -94,6 +94,12 @@ struct Chunk8<kBF16> {
         *reinterpret_cast<uint4*>(static_cast<uint16_t*>(base) + elem_off) =
             make_uint4(raw[0], raw[1], raw[2], raw[3]);
     }
+    // non-temporal variant: measured 3-7 % faster in the pure streaming kernels (apply, N:M), not in the scan
+    __device__ __forceinline__ void store_vec_nt(void* base, int64_t elem_off) const {
+        u32x4 v;
+        v.x = raw[0]; v.y = raw[1]; v.z = raw[2]; v.w = raw[3];
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(static_cast<uint16_t*>(base) + elem_off));
+    }
     __device__ __forceinline__ void store_elems(void* base, int64_t elem_off, int valid) const {
         uint16_t* p = static_cast<uint16_t*>(base) + elem_off;
 #pragma unroll
@@ -134,6 +140,14 @@ struct Chunk8<kF32> {
         uint4* p = reinterpret_cast<uint4*>(static_cast<float*>(base) + elem_off);
         p[0] = make_uint4(raw[0], raw[1], raw[2], raw[3]);
         p[1] = make_uint4(raw[4], raw[5], raw[6], raw[7]);
+    }
+    __device__ __forceinline__ void store_vec_nt(void* base, int64_t elem_off) const {
+        u32x4* p = reinterpret_cast<u32x4*>(static_cast<float*>(base) + elem_off);
+        u32x4 a, b;
+        a.x = raw[0]; a.y = raw[1]; a.z = raw[2]; a.w = raw[3];
+        b.x = raw[4]; b.y = raw[5]; b.z = raw[6]; b.w = raw[7];
+        __builtin_nontemporal_store(a, p);
+        __builtin_nontemporal_store(b, p + 1);
     }
     __device__ __forceinline__ void store_elems(void* base, int64_t elem_off, int valid) const {
         uint32_t* p = static_cast<uint32_t*>(base) + elem_off;

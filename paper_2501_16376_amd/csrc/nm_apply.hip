@@ -104,7 +104,7 @@ __global__ __launch_bounds__(kColThreads) void nm_select_kernel(
         if ((lane & 3) == 0 && widx < mask_words) keep_mask[row * mask_words + widx] = word;
         if (apply && valid) {
             w[r].apply(keep);
-            if (VEC) w[r].store_vec(W, row * ldw + q0);
+            if (VEC) w[r].store_vec_nt(W, row * ldw + q0);
             else w[r].store_elems(W, row * ldw + q0, valid);
         }
     }
@@ -138,7 +138,7 @@ __global__ __launch_bounds__(kColThreads) void apply_kernel(void* __restrict__ W
     for (int r = 0; r < kRows; ++r) {
         if (r < nrows) {
             w[r].apply(keep[r]);
-            if (VEC) w[r].store_vec(W, (row0 + r) * ldw + q0);
+            if (VEC) w[r].store_vec_nt(W, (row0 + r) * ldw + q0);
             else w[r].store_elems(W, (row0 + r) * ldw + q0, valid);
         }
     }
