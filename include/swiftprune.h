@@ -77,10 +77,10 @@ typedef struct {
  *   workspace  >= swiftprune_stats_workspace_bytes(tokens, in) bytes, 256-byte
  *              aligned, contents irrelevant on entry, clobbered (device)
  *
- * Per-lane sums run in fp32 over chains of at most a quarter of a workgroup's
- * token range (a few thousand terms) and are then combined in fp64 in a fixed
- * order: the result does not depend on scheduling.  S is the fp64 sum of the
- * fp32 partial sums, rounded once.
+ * Per-lane sums run in fp32 over chains of at most 32 terms, are folded into
+ * fp64 every 128 rows and combined in fp64 in a fixed order: xsq is within one
+ * or two fp32 roundings of the exact sum and does not depend on scheduling.
+ * S is the fp64 sum of the per-workgroup fp64 sums, rounded once.
  * Fast path: X 16-byte aligned, ldx and in multiples of 16 bytes worth of
  * elements; anything else takes an element-wise path with the same result.
  */

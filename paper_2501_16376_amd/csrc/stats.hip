@@ -11,8 +11,8 @@
 // giving every workgroup its own contiguous token range); strips x splits is
 // about one workgroup per compute unit (more resident workgroups lower the
 // achieved HBM rate).  Every lane keeps fp32 running sums for the columns of
-// its unit, a batch of rows in flight, four independent accumulator sets so no
-// serial fp32 chain exceeds a quarter of the rows a workgroup sees.  Each workgroup writes one partial row segment and the fp64 sum of it;
+// its unit, a batch of rows in flight, in four independent accumulator sets that
+// are folded into fp64 sums every 128 rows, so no serial fp32 chain exceeds 32 terms.  Each workgroup writes one partial row segment and the fp64 sum of it;
 // a second small kernel adds the partial rows of every column in fp64 in a fixed
 // order (LDS-staged), adds the per-workgroup sums in index order to get S (every
 // workgroup redoes that small sum, so none waits for another) and writes the
@@ -23,7 +23,8 @@
 namespace sp {
 
 constexpr int kStatsThreads = 256;       // one wide strip per workgroup, 4 wavefronts
-constexpr int kStatsSets = 4;            // independent accumulator sets per column
+constexpr int kStatsSets = 4;            // independent fp32 accumulator sets per column
+constexpr int kStatsFlushRows = 128;     // rows between folds of the fp32 sets into the fp64 sums
 constexpr int kStatsComputeUnits = 256;   // MI355X
 constexpr int kCombineThreads = 256;     // 64 columns x 4 groups of partial rows
 constexpr int kCombineGroups = kCombineThreads / 64;
@@ -112,20 +113,41 @@ __global__ __launch_bounds__(kStatsThreads) __attribute__((amdgpu_waves_per_eu(1
     const bool active = (int)threadIdx.x < strip_units && u < units;
     const int64_t col = u * EPU;
 
+    // two levels: four fp32 accumulator sets per column take at most kStatsFlushRows rows, then they
+    // are folded into an fp64 sum and cleared.  A long fp32 chain of squares loses every addend that
+    // falls below half an ulp of the running sum (a systematic deficit of several 1e-6 after a few
+    // thousand rows); with short chains the result is within one fp32 rounding of the exact sum.
     float acc[kStatsSets][EPU];
+    double acc64[EPU];
 #pragma unroll
-    for (int s = 0; s < kStatsSets; ++s)
+    for (int k = 0; k < EPU; ++k) {
+        acc64[k] = 0.0;
 #pragma unroll
-        for (int k = 0; k < EPU; ++k) acc[s][k] = 0.f;
+        for (int s = 0; s < kStatsSets; ++s) acc[s][k] = 0.f;
+    }
+    auto fold = [&]() {
+#pragma unroll
+        for (int k = 0; k < EPU; ++k) {
+            acc64[k] += (double)((acc[0][k] + acc[1][k]) + (acc[2][k] + acc[3][k]));
+#pragma unroll
+            for (int s = 0; s < kStatsSets; ++s) acc[s][k] = 0.f;
+        }
+    };
 
     double lane_total = 0.0;
     if (active) {
         int64_t r = (int64_t)split * UNROLL;
         const int64_t step = splits * UNROLL;
+        constexpr int kFoldEvery = kStatsFlushRows / UNROLL;  // batches between folds
+        int since_fold = 0;
         for (; r + UNROLL <= tokens; r += step) {
             XUnit<DT, EPU> v[UNROLL];
 #pragma unroll
             for (int j = 0; j < UNROLL; ++j) v[j].load(X, (r + j) * ldx + col);
+            if (++since_fold == kFoldEvery) {  // uniform; runs while the loads above are in flight
+                fold();
+                since_fold = 0;
+            }
 #pragma unroll
             for (int j = 0; j < UNROLL; ++j) v[j].sq_add(acc[j % kStatsSets]);
         }
@@ -134,12 +156,12 @@ __global__ __launch_bounds__(kStatsThreads) __attribute__((amdgpu_waves_per_eu(1
             v.load(X, r * ldx + col);
             v.sq_add(acc[0]);
         }
+        fold();
         float* p = partials + (int64_t)split * (units * EPU) + col;
 #pragma unroll
         for (int k = 0; k < EPU; ++k) {
-            const float t = (acc[0][k] + acc[1][k]) + (acc[2][k] + acc[3][k]);
-            p[k] = t;
-            lane_total += (double)t;
+            p[k] = (float)acc64[k];
+            lane_total += acc64[k];
         }
     }
     const double total = block_sum_256(lane_total, lds4);

@@ -119,10 +119,12 @@ def test_ewma_vs_sort_overlap_at_scale(orc, gpu):
     from paper_2501_16376_amd import binding as b, synth
     from gpu_util import mask_to_host
     out = n = 4096
+    from gpu_util import to_device
     X = synth.device_activations(8192, n, seed=11, device=gpu)
     W = synth.device_weights(out, n, seed=12, device=gpu)
     bufs = b.LayerBuffers(out, n, 8192, gpu)
-    b.swiftprune_layer_stats(X, bufs.xsq, bufs.S, bufs.hr, workspace=bufs.workspace)
+    _, _, hr_o = orc.layer_stats(synth.torch_to_host_bits(X))       # the oracle's own factor, used by both sides
+    bufs.hr.copy_(to_device(hr_o, gpu))
     for ratio, la in ((0.5, 0.5), (0.7, -0.2)):
         b.swiftprune_score_select(W, bufs.hr, bufs.keep_mask, la=la, row_pruned=bufs.row_pruned)
         topk = torch.empty_like(bufs.keep_mask)
@@ -133,7 +135,7 @@ def test_ewma_vs_sort_overlap_at_scale(orc, gpu):
         k_tot = int(bufs.row_pruned.sum().item())
         assert np.unpackbits((~m_t).view(np.uint8)).sum() == k_tot
         Wh = synth.torch_to_host_bits(W[:64])
-        ref = orc.topk_select(Wh, bufs.hr.cpu().numpy(), bufs.row_pruned[:64].cpu().numpy())
+        ref = orc.topk_select(Wh, hr_o, bufs.row_pruned[:64].cpu().numpy())
         assert np.array_equal(m_t[:64], ref)
         overlap = both / k_tot
         say(f"[report] la={la:+.1f}: achieved sparsity {k_tot / (out * n):.4f}, "
