@@ -204,7 +204,7 @@ int swiftprune_compact_nm(const void* W, int64_t out, int64_t in, int64_t ldw, s
                           const uint32_t* keep_mask, int n_keep, int m_group, void* values,
                           uint32_t* meta, void* hip_stream) {
     if (W == nullptr || keep_mask == nullptr || values == nullptr || meta == nullptr) return SP_EINVAL;
-    if (out <= 0 || in <= 0 || ldw < in || !dtype_ok((int)dt) || out > 65535 * (int64_t)65535) return SP_EINVAL;
+    if (out <= 0 || in <= 0 || ldw < in || !dtype_ok((int)dt)) return SP_EINVAL;
     if (!nm_pattern_ok(in, n_keep, m_group)) return SP_EINVAL;
     if (reinterpret_cast<uintptr_t>(W) % elem_size((int)dt) != 0 ||
         reinterpret_cast<uintptr_t>(values) % elem_size((int)dt) != 0)

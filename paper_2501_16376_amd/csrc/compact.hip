@@ -26,14 +26,15 @@ __device__ __forceinline__ void store_raw(void* p, int64_t idx, uint32_t v) {
     else static_cast<uint32_t*>(p)[idx] = v;
 }
 
-// grid = (ceil(chunks / 64), out), block = 64; chunk = 32 groups
+// grid = ceil(chunks / 64) * out (one dimension, chunk block fastest), block = 64; chunk = 32 groups
 template <int DT>
 __global__ __launch_bounds__(64) void compact_nm_kernel(const void* __restrict__ W, int64_t in, int64_t ldw,
                                                         const uint32_t* __restrict__ keep_mask, int n_keep,
                                                         int m_group, void* __restrict__ values,
-                                                        uint32_t* __restrict__ meta, int64_t meta_words) {
-    const int64_t row = blockIdx.y;
-    const int64_t chunk = (int64_t)blockIdx.x * 64 + threadIdx.x;
+                                                        uint32_t* __restrict__ meta, int64_t meta_words,
+                                                        unsigned chunk_blocks) {
+    const int64_t row = blockIdx.x / chunk_blocks;
+    const int64_t chunk = (int64_t)(blockIdx.x % chunk_blocks) * 64 + threadIdx.x;
     const int64_t groups = in / m_group;
     const int64_t g0 = chunk * 32;
     if (g0 >= groups) return;
@@ -81,9 +82,10 @@ template <int DT>
 __global__ __launch_bounds__(64) void expand_nm_kernel(const void* __restrict__ values,
                                                        const uint32_t* __restrict__ meta, int64_t in,
                                                        int n_keep, int m_group, int64_t meta_words,
-                                                       void* __restrict__ W_out, int64_t ldw) {
-    const int64_t row = blockIdx.y;
-    const int64_t chunk = (int64_t)blockIdx.x * 64 + threadIdx.x;
+                                                       void* __restrict__ W_out, int64_t ldw,
+                                                       unsigned chunk_blocks) {
+    const int64_t row = blockIdx.x / chunk_blocks;
+    const int64_t chunk = (int64_t)(blockIdx.x % chunk_blocks) * 64 + threadIdx.x;
     const int64_t groups = in / m_group;
     const int64_t g0 = chunk * 32;
     if (g0 >= groups) return;
@@ -108,28 +110,32 @@ hipError_t launch_compact_nm(const void* W, int64_t out, int64_t in, int64_t ldw
                              const uint32_t* keep_mask, int n_keep, int m_group, void* values,
                              uint32_t* meta, hipStream_t stream) {
     const int64_t chunks = (in / m_group + 31) / 32;
-    dim3 grid((unsigned)((chunks + 63) / 64), (unsigned)out);
+    const unsigned chunk_blocks = (unsigned)((chunks + 63) / 64);
+    if ((int64_t)chunk_blocks * out > 0x7fffffff) return hipErrorInvalidValue;
+    dim3 grid((unsigned)(chunk_blocks * out));
     const int64_t mw = nm_meta_words(in, n_keep, m_group);
     if (dt == kBF16)
         hipLaunchKernelGGL(compact_nm_kernel<kBF16>, grid, dim3(64), 0, stream, W, in, ldw, keep_mask, n_keep,
-                           m_group, values, meta, mw);
+                           m_group, values, meta, mw, chunk_blocks);
     else
         hipLaunchKernelGGL(compact_nm_kernel<kF32>, grid, dim3(64), 0, stream, W, in, ldw, keep_mask, n_keep,
-                           m_group, values, meta, mw);
+                           m_group, values, meta, mw, chunk_blocks);
     return hipGetLastError();
 }
 
 hipError_t launch_expand_nm(const void* values, const uint32_t* meta, int64_t out, int64_t in, int dt,
                             int n_keep, int m_group, void* W_out, int64_t ldw, hipStream_t stream) {
     const int64_t chunks = (in / m_group + 31) / 32;
-    dim3 grid((unsigned)((chunks + 63) / 64), (unsigned)out);
+    const unsigned chunk_blocks = (unsigned)((chunks + 63) / 64);
+    if ((int64_t)chunk_blocks * out > 0x7fffffff) return hipErrorInvalidValue;
+    dim3 grid((unsigned)(chunk_blocks * out));
     const int64_t mw = nm_meta_words(in, n_keep, m_group);
     if (dt == kBF16)
         hipLaunchKernelGGL(expand_nm_kernel<kBF16>, grid, dim3(64), 0, stream, values, meta, in, n_keep, m_group,
-                           mw, W_out, ldw);
+                           mw, W_out, ldw, chunk_blocks);
     else
         hipLaunchKernelGGL(expand_nm_kernel<kF32>, grid, dim3(64), 0, stream, values, meta, in, n_keep, m_group,
-                           mw, W_out, ldw);
+                           mw, W_out, ldw, chunk_blocks);
     return hipGetLastError();
 }
 

@@ -63,16 +63,18 @@ __device__ __forceinline__ uint32_t nm_keep_bits16(const float* L, int n_prune, 
     return keep;
 }
 
-// grid = (ceil(chunks / 256), ceil(out / kRows)), block = 256
+// A tile is kRows rows x 256 chunks (2048 columns).  grid = col_tiles * row_groups (one dimension, column
+// tile fastest, so consecutive workgroups touch consecutive memory), block = 256.
 template <int DT, bool VEC, int M>
 __global__ __launch_bounds__(kColThreads) void nm_select_kernel(
     void* __restrict__ W, int64_t out, int64_t in, int64_t ldw, const float* __restrict__ hr,
-    int n_prune, uint32_t* __restrict__ keep_mask, float* __restrict__ scores, int apply) {
+    int n_prune, uint32_t* __restrict__ keep_mask, float* __restrict__ scores, int apply,
+    unsigned col_tiles) {
     const int lane = threadIdx.x & (kWave - 1);
-    const int64_t chunk = (int64_t)blockIdx.x * kColThreads + threadIdx.x;
+    const int64_t chunk = (int64_t)(blockIdx.x % col_tiles) * kColThreads + threadIdx.x;
     const int64_t q0 = chunk * 8;
     const int valid = (int)min((int64_t)8, max((int64_t)0, in - q0));
-    const int64_t row0 = (int64_t)blockIdx.y * kRows;
+    const int64_t row0 = (int64_t)(blockIdx.x / col_tiles) * kRows;
     const int64_t mask_words = (in + 31) >> 5;
     const int nrows = (int)min((int64_t)kRows, out - row0);
 
@@ -114,12 +116,13 @@ __global__ __launch_bounds__(kColThreads) void nm_select_kernel(
 template <int DT, bool VEC>
 __global__ __launch_bounds__(kColThreads) void apply_kernel(void* __restrict__ W, int64_t out, int64_t in,
                                                            int64_t ldw,
-                                                           const uint32_t* __restrict__ keep_mask) {
-    const int64_t chunk = (int64_t)blockIdx.x * kColThreads + threadIdx.x;
+                                                           const uint32_t* __restrict__ keep_mask,
+                                                           unsigned col_tiles) {
+    const int64_t chunk = (int64_t)(blockIdx.x % col_tiles) * kColThreads + threadIdx.x;
     const int64_t q0 = chunk * 8;
     const int valid = (int)min((int64_t)8, max((int64_t)0, in - q0));
     if (valid == 0) return;
-    const int64_t row0 = (int64_t)blockIdx.y * kRows;
+    const int64_t row0 = (int64_t)(blockIdx.x / col_tiles) * kRows;
     const int64_t mask_words = (in + 31) >> 5;
     const int nrows = (int)min((int64_t)kRows, out - row0);
     const int shift = (int)(q0 & 31);
@@ -149,23 +152,25 @@ static hipError_t launch_nm_t(const void* W, int64_t out, int64_t in, int64_t ld
                               int n_keep, int m_group, uint32_t* keep_mask, float* scores, bool apply,
                               hipStream_t stream) {
     const int64_t chunks = (in + 7) / 8;
-    // a whole number of quads per row so that every mask word is assembled by a full quad
-    dim3 grid((unsigned)((chunks + kColThreads - 1) / kColThreads), (unsigned)((out + kRows - 1) / kRows));
+    const unsigned col_tiles = (unsigned)((chunks + kColThreads - 1) / kColThreads);
+    const int64_t tiles = (int64_t)col_tiles * ((out + kRows - 1) / kRows);
+    if (tiles > 0x7fffffff) return hipErrorInvalidValue;
+    dim3 grid((unsigned)tiles);
     void* Wm = const_cast<void*>(W);
     const int n_prune = m_group - n_keep;
     const int ap = apply ? 1 : 0;
     switch (m_group) {
         case 4:
             hipLaunchKernelGGL((nm_select_kernel<DT, VEC, 4>), grid, dim3(kColThreads), 0, stream, Wm, out, in,
-                               ldw, hr, n_prune, keep_mask, scores, ap);
+                               ldw, hr, n_prune, keep_mask, scores, ap, col_tiles);
             break;
         case 8:
             hipLaunchKernelGGL((nm_select_kernel<DT, VEC, 8>), grid, dim3(kColThreads), 0, stream, Wm, out, in,
-                               ldw, hr, n_prune, keep_mask, scores, ap);
+                               ldw, hr, n_prune, keep_mask, scores, ap, col_tiles);
             break;
         case 16:
             hipLaunchKernelGGL((nm_select_kernel<DT, VEC, 16>), grid, dim3(kColThreads), 0, stream, Wm, out, in,
-                               ldw, hr, n_prune, keep_mask, scores, ap);
+                               ldw, hr, n_prune, keep_mask, scores, ap, col_tiles);
             break;
         default:
             return hipErrorInvalidValue;
@@ -186,13 +191,16 @@ hipError_t launch_nm_select(const void* W, int64_t out, int64_t in, int64_t ldw,
 hipError_t launch_apply(void* W, int64_t out, int64_t in, int64_t ldw, int dt, bool vec,
                         const uint32_t* keep_mask, hipStream_t stream) {
     const int64_t chunks = (in + 7) / 8;
-    dim3 grid((unsigned)((chunks + kColThreads - 1) / kColThreads), (unsigned)((out + kRows - 1) / kRows));
+    const unsigned col_tiles = (unsigned)((chunks + kColThreads - 1) / kColThreads);
+    const int64_t tiles = (int64_t)col_tiles * ((out + kRows - 1) / kRows);
+    if (tiles > 0x7fffffff) return hipErrorInvalidValue;
+    dim3 grid((unsigned)tiles);
     if (dt == kBF16) {
-        if (vec) hipLaunchKernelGGL((apply_kernel<kBF16, true>), grid, dim3(kColThreads), 0, stream, W, out, in, ldw, keep_mask);
-        else hipLaunchKernelGGL((apply_kernel<kBF16, false>), grid, dim3(kColThreads), 0, stream, W, out, in, ldw, keep_mask);
+        if (vec) hipLaunchKernelGGL((apply_kernel<kBF16, true>), grid, dim3(kColThreads), 0, stream, W, out, in, ldw, keep_mask, col_tiles);
+        else hipLaunchKernelGGL((apply_kernel<kBF16, false>), grid, dim3(kColThreads), 0, stream, W, out, in, ldw, keep_mask, col_tiles);
     } else {
-        if (vec) hipLaunchKernelGGL((apply_kernel<kF32, true>), grid, dim3(kColThreads), 0, stream, W, out, in, ldw, keep_mask);
-        else hipLaunchKernelGGL((apply_kernel<kF32, false>), grid, dim3(kColThreads), 0, stream, W, out, in, ldw, keep_mask);
+        if (vec) hipLaunchKernelGGL((apply_kernel<kF32, true>), grid, dim3(kColThreads), 0, stream, W, out, in, ldw, keep_mask, col_tiles);
+        else hipLaunchKernelGGL((apply_kernel<kF32, false>), grid, dim3(kColThreads), 0, stream, W, out, in, ldw, keep_mask, col_tiles);
     }
     return hipGetLastError();
 }

@@ -179,3 +179,39 @@ def test_compact_and_expand_nm(orc, gpu, out, n, dtype):
     torch.cuda.synchronize()
     v_o, m_o = orc.compact_nm(Wh, mask_to_host(mask), 2, 4)
     assert np.array_equal(synth.torch_to_host_bits(vals), v_o) and np.array_equal(mask_to_host(meta), m_o)
+
+
+def test_very_tall_matrix(orc, gpu):
+    """600001 rows x 16 columns: every kernel indexes rows through a one-dimensional grid."""
+    import torch
+    from paper_2501_16376_amd import binding as b, synth
+    from gpu_util import to_device, mask_to_host, check_ewma_mask
+    out, n = 600001, 16
+    Wh, hr, W, hr_dev = _inputs(orc, gpu, out, n, 64, seed=99)
+    mask = torch.empty((out, 1), dtype=torch.int32, device=gpu)
+    cnt = torch.empty(out, dtype=torch.int32, device=gpu)
+    b.swiftprune_score_select(W, hr_dev, mask, la=0.5, row_pruned=cnt, flags=b.SP_SEQUENTIAL_ORDER)
+    torch.cuda.synchronize()
+    mask_o, cnt_o, _ = orc.ewma_select(Wh, hr, A, B, 0.5)
+    assert np.array_equal(mask_to_host(mask), mask_o) and np.array_equal(cnt.cpu().numpy(), cnt_o)
+    b.swiftprune_score_select(W, hr_dev, mask, la=0.5, row_pruned=cnt)
+    torch.cuda.synchronize()
+    check_ewma_mask(orc, Wh, hr, A, B, 0.5, mask_to_host(mask), cnt.cpu().numpy())
+    b.swiftprune_nm_select(W, hr_dev, 2, 4, mask)
+    torch.cuda.synchronize()
+    nm_o, _ = orc.nm_select(Wh, hr, 2, 4)
+    assert np.array_equal(mask_to_host(mask), nm_o)
+    vals = torch.empty((out, n // 2), dtype=torch.bfloat16, device=gpu)
+    meta = torch.empty((out, b.swiftprune_nm_meta_words(n, 2, 4)), dtype=torch.int32, device=gpu)
+    b.swiftprune_compact_nm(W, mask, 2, 4, vals, meta)
+    dense = torch.empty((out, n), dtype=torch.bfloat16, device=gpu)
+    b.swiftprune_expand_nm(vals, meta, n, 2, 4, dense)
+    W2 = W.clone()
+    b.swiftprune_apply(W2, mask)
+    torch.cuda.synchronize()
+    ref = orc.apply(Wh.copy(), nm_o)
+    assert np.array_equal(synth.torch_to_host_bits(W2), ref)
+    assert np.array_equal(synth.torch_to_host_bits(dense), ref)
+    b.swiftprune_topk_select(W, hr_dev, mask, k_uniform=5)
+    torch.cuda.synchronize()
+    assert np.array_equal(mask_to_host(mask), orc.topk_select(Wh, hr, 5))
