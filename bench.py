@@ -44,6 +44,9 @@ def parse():
     ap.add_argument("--streams", type=int, default=1, choices=[1, 2],
                     help="2 = statistics on one stream, selection+apply on another (double-buffered factors), "
                          "so a layer's selection overlaps the next layer's statistics")
+    ap.add_argument("--layer-sweep", action="store_true",
+                    help="also time every distinct layer shape of the block on its own (statistics + "
+                         "selection/apply) and add the per-layer HBM fractions to the JSON line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not bracket the statistics launches with events")
@@ -248,10 +251,54 @@ def main():
                          "not the same machine, weights or calibration set",
     }
 
+    if args.layer_sweep:
+        result["layer_sweep"] = layer_sweep(sp, torch, block, X, weights, pristine, bufs, T, nm, la, stream)
+
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(block, X, pristine, T, nm, la)
 
     print(json.dumps(result))
+
+
+def layer_sweep(sp, torch, block, X, weights, pristine, bufs, T, nm, la, stream, reps=20):
+    """Each distinct layer shape of the block on its own: statistics, then selection + apply, timed with
+    events over `reps` layers drawn from different blocks of the stack (different weight buffers, so no
+    launch re-reads a cached matrix); algorithmic bytes / time / 8 TB/s per layer."""
+    n_layers = len(block)
+    n_blocks = len(weights) // n_layers
+    out_rows = []
+    seen = set()
+    for li, (name, out, n) in enumerate(block):
+        if (out, n) in seen:
+            continue
+        seen.add((out, n))
+        b = bufs[(out, n)]
+        idxs = [((r % n_blocks) * n_layers + li) for r in range(reps)]
+        for i in set(idxs):
+            weights[i].copy_(pristine[i])
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3 * reps)]
+        for r, i in enumerate(idxs):
+            ev[3 * r].record(stream)
+            sp.swiftprune_layer_stats(X[INPUT_OF[name]], b.xsq, b.S, b.hr, workspace=b.workspace, stream=stream)
+            ev[3 * r + 1].record(stream)
+            if nm is None:
+                sp.swiftprune_score_select(weights[i], b.hr, b.keep_mask, la=la, row_pruned=b.row_pruned,
+                                           flags=sp.SP_APPLY_INPLACE, stream=stream)
+            else:
+                sp.swiftprune_nm_select(weights[i], b.hr, nm[0], nm[1], b.keep_mask,
+                                        flags=sp.SP_APPLY_INPLACE, stream=stream)
+            ev[3 * r + 2].record(stream)
+        torch.cuda.synchronize()
+        t_stats = sum(ev[3 * r].elapsed_time(ev[3 * r + 1]) for r in range(reps)) / reps * 1e3
+        t_sel = sum(ev[3 * r + 1].elapsed_time(ev[3 * r + 2]) for r in range(reps)) / reps * 1e3
+        stats_b = T * n * 2
+        sel_b = out * n * 4 + out * n // 8 + n * 4
+        out_rows.append({"layer": f"{name} {out}x{n}", "stats_us": round(t_stats, 1), "select_apply_us": round(t_sel, 1),
+                         "stats_hbm_frac": round(stats_b / t_stats / 1e6 / HBM_PEAK_GBS * 1e3, 4),
+                         "select_apply_hbm_frac": round(sel_b / t_sel / 1e6 / HBM_PEAK_GBS * 1e3, 4),
+                         "layer_hbm_frac": round((stats_b + sel_b) / (t_stats + t_sel) / 1e6 / HBM_PEAK_GBS * 1e3, 4)})
+    return out_rows
 
 
 def committed_traffic():
