@@ -182,6 +182,51 @@ def test_shapes(orc, gpu, out, n, tokens, dtype, pad):
     say(f"  tolerated scan differences: {t}")
 
 
+def test_random_small_shapes(orc, gpu):
+    """Forty seeded random shapes (1-40 rows, 1-1500 columns, 1-200 tokens, both dtypes, random row pitch):
+    statistics to 1e-5, strict-order / N:M / apply bit-exact, scan path under the rounding rule."""
+    import torch
+    from paper_2501_16376_amd import binding as b, synth
+    from gpu_util import to_device, check_ewma_mask, mask_to_host
+    rng = np.random.default_rng(2024)
+    for case in range(40):
+        out = int(rng.integers(1, 41))
+        n = int(rng.integers(1, 1501))
+        if case % 3 == 0:
+            n = max(8, n // 8 * 8)                                    # exercise the vector path too
+        tokens = int(rng.integers(1, 201))
+        dtype = "bf16" if case % 2 == 0 else "f32"
+        pad = int(rng.choice([0, 0, 8, 3]))
+        la = float(rng.choice([0.5, 0.2, -0.2, -0.9, 1.1]))
+        say(f"[case {case}] out={out} in={n} tokens={tokens} {dtype} pad={pad} la={la}")
+        Wh, Xh = synth.layer_inputs(out, n, tokens, seed=5000 + case, dtype=dtype)
+        Wp = np.zeros((out, n + pad), dtype=Wh.dtype)
+        Wp[:, :n] = Wh
+        Xp = np.zeros((tokens, n + pad), dtype=Xh.dtype)
+        Xp[:, :n] = Xh
+        W_dev, X_dev = to_device(Wp, gpu)[:, :n], to_device(Xp, gpu)[:, :n]
+        xsq_o, S_o, hr_o = orc.layer_stats(Xh)
+        xsq_g, S_g, hr_g = _stats_gpu(X_dev, n)
+        assert np.allclose(xsq_g, xsq_o, rtol=1e-5, atol=0) and abs(S_g - S_o) <= 1e-5 * abs(S_o)
+        assert np.allclose(hr_g, hr_o, rtol=1e-5, atol=0)
+        hr_dev = to_device(hr_o, gpu)
+        mask_o, cnt_o, _ = orc.ewma_select(Wh, hr_o, A, B, la)
+        m_seq, c_seq, _ = _select_gpu(W_dev, hr_dev, la, flags=b.SP_SEQUENTIAL_ORDER)
+        assert np.array_equal(m_seq, mask_o) and np.array_equal(c_seq, cnt_o)
+        m_scan, c_scan, _ = _select_gpu(W_dev, hr_dev, la)
+        check_ewma_mask(orc, Wh, hr_o, A, B, la, m_scan, c_scan)
+        for nk, m in ((2, 4), (4, 8), (5, 16)):
+            if n % m == 0:
+                nm_g, _ = _nm_gpu(W_dev, hr_dev, nk, m)
+                assert np.array_equal(nm_g, orc.nm_select(Wh, hr_o, nk, m)[0]), (nk, m)
+        W2 = to_device(Wp, gpu)[:, :n]
+        mk = torch.empty((out, (n + 31) // 32), dtype=torch.int32, device=gpu)
+        b.swiftprune_score_select(W2, hr_dev, mk, la=la, flags=b.SP_APPLY_INPLACE)
+        torch.cuda.synchronize()
+        assert np.array_equal(synth.torch_to_host_bits(W2), orc.apply(Wh.copy(), mask_to_host(mk)))
+        assert np.all(synth.torch_to_host_bits(W2._base)[:, n:] == 0)
+
+
 def test_other_alpha_beta(orc, gpu):
     """alpha != beta, large and small decay, negative and large la."""
     from paper_2501_16376_amd import binding as b, synth
