@@ -149,6 +149,23 @@ def pin_step_response(orc, L=None):
     assert np.isclose(dev[k], 0.3 * abs(est[k] - c2), rtol=1e-14)
 
 
+def pin_tracks_mean_and_deviation(orc, L=None):
+    """The tracking figure of Sec. 4.2: on a long stationary row est follows the mean of the scores and
+    dev the mean absolute gap between est and the scores (both are unbiased EWMAs of those quantities)."""
+    rng = _rng(13)
+    Lrow = rng.chisquare(1, size=40000) * 2.5
+    for alpha, beta in ((0.125, 0.125), (0.05, 0.2)):
+        _, est, dev = orc.ewma_row(Lrow, alpha, beta, 4.0, precision="f64", L=L)
+        warm = 500
+        assert abs(est[warm:].mean() / Lrow[warm:].mean() - 1) < 0.02
+        gap = np.abs(est[warm:] - Lrow[warm:]).mean()
+        assert abs(dev[warm:].mean() / gap - 1) < 0.02
+        # a slower est (smaller alpha) is smoother
+    _, e_fast, _ = orc.ewma_row(Lrow, 0.5, 0.125, 4.0, precision="f64", L=L)
+    _, e_slow, _ = orc.ewma_row(Lrow, 0.02, 0.125, 4.0, precision="f64", L=L)
+    assert e_slow[500:].std() < 0.3 * e_fast[500:].std()
+
+
 # ------------------------------------------------------------------ statistics and score
 def pin_stats_library_sum(orc, L=None):
     """Step 1 against numpy's float64 column sum; bf16 and fp32 inputs, with a row pitch."""
@@ -466,7 +483,7 @@ def pin_compact_nm(orc, L=None):
     assert np.array_equal(orc.expand_nm(vals, meta, 8, 2, 4, L=L), [[0, 11, 0, 0, 0, 0, 0, 0]])
 
 
-ALL_PINS = [pin_topk_is_library_sort, pin_compact_nm, pin_worked_rows, pin_closed_form, pin_constant_row, pin_first_two_elements,
+ALL_PINS = [pin_topk_is_library_sort, pin_compact_nm, pin_tracks_mean_and_deviation, pin_worked_rows, pin_closed_form, pin_constant_row, pin_first_two_elements,
             pin_monotone_in_la, pin_step_response, pin_stats_library_sum, pin_inverse_identity,
             pin_float_factor_matches_double, pin_select_metamorphic,
             pin_uniform_energy_reduces_to_magnitude, pin_nm_invariants,
