@@ -12,7 +12,8 @@
 // about one workgroup per compute unit (more resident workgroups lower the
 // achieved HBM rate).  Every lane keeps fp32 running sums for the columns of
 // its unit, a batch of rows in flight, in four independent accumulator sets that
-// are folded into fp64 sums every 128 rows, so no serial fp32 chain exceeds 32 terms.  Each workgroup writes one partial row segment and the fp64 sum of it;
+// are folded into fp64 sums every 128 rows, so no serial fp32 chain exceeds 32
+// terms.  Each workgroup writes one partial row segment and the fp64 sum of it;
 // a second small kernel adds the partial rows of every column in fp64 in a fixed
 // order (LDS-staged), adds the per-workgroup sums in index order to get S (every
 // workgroup redoes that small sum, so none waits for another) and writes the
@@ -25,7 +26,7 @@ namespace sp {
 constexpr int kStatsThreads = 256;       // one wide strip per workgroup, 4 wavefronts
 constexpr int kStatsSets = 4;            // independent fp32 accumulator sets per column
 constexpr int kStatsFlushRows = 128;     // rows between folds of the fp32 sets into the fp64 sums
-constexpr int kStatsComputeUnits = 256;   // MI355X
+constexpr int kStatsComputeUnits = 256;   // compute units of an MI355X
 constexpr int kCombineThreads = 256;     // 64 columns x 4 groups of partial rows
 constexpr int kCombineGroups = kCombineThreads / 64;
 
