@@ -115,8 +115,8 @@ int swiftprune_score_select(const void *W, int64_t out, int64_t in, int64_t ldw,
                             uint32_t flags, void *hip_stream);
 
 /*
- * Threshold tuning (Sec. 3.1: the ratio -> la table covers 50..90 % only and "la can be tuned for
- * different levels of sparsity").  With S fixed, est and dev do not depend on la, so one pass over W
+ * Threshold tuning (Sec. 3.1: the ratio -> la table covers 50..90 % only, and la is described as the
+ * knob that sets the level of sparsity).  With S fixed, est and dev do not depend on la, so one pass over W
  * counts the pruned weights for several candidate la at once.
  *
  *   la       host array of n_la (1..16) finite candidates
@@ -193,6 +193,20 @@ int swiftprune_compact_nm(const void *W, int64_t out, int64_t in, int64_t ldw, s
  * positions and +0 everywhere else. */
 int swiftprune_expand_nm(const void *values, const uint32_t *meta, int64_t out, int64_t in, sp_dtype dt,
                          int n_keep, int m_group, void *W_out, int64_t ldw_out, void *hip_stream);
+
+/*
+ * Diagnostic: the est and dev sequences of the EWMA walk (Sec. 3.2; state-update table of Sec. 3.1; the
+ * tracking figure of Sec. 4.2 plots them against the mean and the mean deviation of the scores).
+ *
+ *   est, dev   [out, in] fp32, row-major with pitch in: the state AFTER the update with element q;
+ *              either may be null, not both                                      (device, write)
+ *   alpha, beta in (0, 1].  la takes no part: the two sequences do not depend on it.
+ * Evaluated with the same wavefront scans as swiftprune_score_select's default path, so the values
+ * differ from a sequential fp32 walk by a few ulp.  Asynchronous on hip_stream.
+ */
+int swiftprune_ewma_trace(const void *W, int64_t out, int64_t in, int64_t ldw, sp_dtype dt,
+                          const float *hr, float alpha, float beta, float *est, float *dev,
+                          void *hip_stream);
 
 /* ---- host helpers (no device work) ---- */
 

@@ -50,7 +50,7 @@ static inline float load_elem(const void *base, int64_t idx, int dt)
 
 /* ------------------------------------------------------------------ */
 /* Step 1: calibration statistics (Algorithm 1, first statement;        */
-/* Sec. 3.1 "S is the sum of all x_i^2").                               */
+/* Sec. 3.1 defines S as the sum of the squared activations).           */
 /* ------------------------------------------------------------------ */
 
 /*
@@ -222,9 +222,9 @@ void oracle_ewma_select_literal_f32(const void *W, int64_t out, int64_t in, int6
 }
 
 /* ------------------------------------------------------------------ */
-/* Exact selection by sorting (Sec. 3.1: "sort the L values of all      */
-/* weights and eliminate those with the smallest L values") - the       */
-/* O(n log n) rule the EWMA walk replaces; used as a comparator.        */
+/* Exact selection by sorting (Sec. 3.1: order a row's scores and drop  */
+/* the lowest ones) - the O(n log n) rule the EWMA walk replaces; used  */
+/* as a comparator.                                                     */
 /* ------------------------------------------------------------------ */
 
 typedef struct {

@@ -20,7 +20,7 @@ SP_OK, SP_EINVAL, SP_ENOSPC, SP_EHIP, SP_ERANGE = 0, -1, -2, -3, -4
 SP_SEQUENTIAL_ORDER, SP_APPLY_INPLACE = 1, 2
 
 EXPORTS = ("swiftprune_layer_stats", "swiftprune_score_select", "swiftprune_nm_select",
-           "swiftprune_apply", "swiftprune_count_pruned", "swiftprune_calibrate_la", "swiftprune_topk_select", "swiftprune_compact_nm", "swiftprune_expand_nm", "swiftprune_nm_meta_words", "swiftprune_la_for_sparsity", "swiftprune_stats_workspace_bytes",
+           "swiftprune_apply", "swiftprune_ewma_trace", "swiftprune_count_pruned", "swiftprune_calibrate_la", "swiftprune_topk_select", "swiftprune_compact_nm", "swiftprune_expand_nm", "swiftprune_nm_meta_words", "swiftprune_la_for_sparsity", "swiftprune_stats_workspace_bytes",
            "swiftprune_strerror", "swiftprune_version")
 
 
@@ -57,6 +57,8 @@ def load_library(path: str | None = None) -> C.CDLL:
     L.swiftprune_nm_select.restype = i32
     L.swiftprune_apply.argtypes = [vp, i64, i64, i64, i32, vp, vp]
     L.swiftprune_apply.restype = i32
+    L.swiftprune_ewma_trace.argtypes = [vp, i64, i64, i64, i32, vp, f, f, vp, vp, vp]
+    L.swiftprune_ewma_trace.restype = i32
     L.swiftprune_count_pruned.argtypes = [vp, i64, i64, i64, i32, vp, f, f, C.POINTER(C.c_float), i32, vp, vp]
     L.swiftprune_count_pruned.restype = i32
     L.swiftprune_calibrate_la.argtypes = [vp, i64, i64, i64, i32, vp, f, f, f, f, f, f, vp,
@@ -186,6 +188,17 @@ def swiftprune_nm_select(W, hr, n_keep: int, m_group: int, keep_mask, scores=Non
         _vec(keep_mask, torch.int32, out * words, "keep_mask"),
         _vec(scores, torch.float32, out * n_in, "scores"), int(flags), _stream(stream))
     _check(code, "swiftprune_nm_select")
+
+
+def swiftprune_ewma_trace(W, hr, est=None, dev=None, alpha: float = 0.125, beta: float = 0.125, stream=None):
+    """est[out, in], dev[out, in] (fp32 GPU tensors, either may be None) = EWMA state after each weight."""
+    import torch
+    ptr, out, n_in, ldw, dt = _matrix(W)
+    code = load_library().swiftprune_ewma_trace(
+        ptr, out, n_in, ldw, dt, _vec(hr, torch.float32, n_in, "hr"), float(alpha), float(beta),
+        _vec(est, torch.float32, out * n_in, "est"), _vec(dev, torch.float32, out * n_in, "dev"),
+        _stream(stream))
+    _check(code, "swiftprune_ewma_trace")
 
 
 def swiftprune_count_pruned(W, hr, la_candidates, counts, alpha: float = 0.125, beta: float = 0.125,

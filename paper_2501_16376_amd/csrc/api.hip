@@ -120,6 +120,21 @@ int swiftprune_score_select(const void* W, int64_t out, int64_t in, int64_t ldw,
     return e == hipSuccess ? SP_OK : SP_EHIP;
 }
 
+int swiftprune_ewma_trace(const void* W, int64_t out, int64_t in, int64_t ldw, sp_dtype dt,
+                          const float* hr, float alpha, float beta, float* est, float* dev,
+                          void* hip_stream) {
+    if (W == nullptr || hr == nullptr || (est == nullptr && dev == nullptr)) return SP_EINVAL;
+    if (out <= 0 || in <= 0 || ldw < in || !dtype_ok((int)dt)) return SP_EINVAL;
+    if (!(alpha > 0.0f && alpha <= 1.0f) || !(beta > 0.0f && beta <= 1.0f)) return SP_EINVAL;
+    if (reinterpret_cast<uintptr_t>(W) % elem_size((int)dt) != 0) return SP_EINVAL;
+    if (reinterpret_cast<uintptr_t>(est) % 4 != 0 || reinterpret_cast<uintptr_t>(dev) % 4 != 0) return SP_EINVAL;
+    const bool vec = weight_vec_ok(W, in, ldw, (int)dt, hr, est) && (dev == nullptr || aligned16(dev));
+    const sp::EwmaConsts c = sp::make_ewma_consts(alpha, beta, 0.0f);
+    const hipError_t e = sp::launch_ewma_trace(W, out, in, ldw, (int)dt, vec, hr, c, est, dev,
+                                               static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? SP_OK : SP_EHIP;
+}
+
 int swiftprune_count_pruned(const void* W, int64_t out, int64_t in, int64_t ldw, sp_dtype dt,
                             const float* hr, float alpha, float beta, const float* la, int n_la,
                             unsigned long long* counts, void* hip_stream) {

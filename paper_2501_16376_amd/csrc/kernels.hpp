@@ -49,6 +49,11 @@ hipError_t launch_ewma_sequential(const void* W, int64_t out, int64_t in, int64_
                                   uint32_t* keep_mask, int32_t* row_pruned, float* scores, bool apply,
                                   hipStream_t stream);
 
+// ---- est / dev sequences written out (diagnostic) ----
+hipError_t launch_ewma_trace(const void* W, int64_t out, int64_t in, int64_t ldw, int dt, bool vec,
+                             const float* hr, const EwmaConsts& c, float* est, float* dev,
+                             hipStream_t stream);
+
 // ---- threshold calibration (count the pruned weights for up to 16 candidate la in one pass) ----
 hipError_t launch_count_pruned(const void* W, int64_t out, int64_t in, int64_t ldw, int dt, bool vec,
                                const float* hr, const EwmaConsts& c, const float* la, int n_la,

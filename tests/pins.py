@@ -401,7 +401,7 @@ def pin_apply(orc, L=None):
 
 
 def pin_sort_comparator(orc, L=None):
-    """The EWMA rule stands in for 'sort the scores and drop the smallest' (Sec. 3.1): with k = the
+    """The EWMA rule stands in for sorting the scores and dropping the lowest (Sec. 3.1): with k = the
     number EWMA prunes in a row, most of them are among the k smallest scores; and the la table of the
     paper orders the achieved sparsity.  Returns the measured numbers for reporting."""
     from paper_2501_16376_amd import synth

@@ -100,6 +100,11 @@ def test_argument_checks_do_not_launch(lib):
     assert nm(p, 8, 8, 8, 1, p, 0, 4, p, None, 0, None) == E
     assert nm(p, 8, 12, 12, 1, p, 4, 8, p, None, 0, None) == E        # in % m != 0
     assert nm(p, 8, 8, 8, 1, p, 2, 4, p, None, 1, None) == E          # strict-order flag not valid here
+    tr = lib.swiftprune_ewma_trace
+    assert tr(p, 8, 8, 8, 1, p, 0.125, 0.125, None, None, None) == E         # nothing to write
+    assert tr(None, 8, 8, 8, 1, p, 0.125, 0.125, p, p, None) == E
+    assert tr(p, 8, 8, 8, 1, p, 0.0, 0.125, p, p, None) == E
+    assert tr(p, 8, 8, 8, 1, p, 0.125, 0.125, p + 2, p, None) == E           # misaligned float pointer
     cp = lib.swiftprune_count_pruned
     las = (C.c_float * 3)(0.5, 0.2, -0.2)
     assert cp(p, 8, 8, 8, 1, p, 0.125, 0.125, las, 0, p, None) == E          # n_la < 1

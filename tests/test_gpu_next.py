@@ -215,3 +215,32 @@ def test_very_tall_matrix(orc, gpu):
     b.swiftprune_topk_select(W, hr_dev, mask, k_uniform=5)
     torch.cuda.synchronize()
     assert np.array_equal(mask_to_host(mask), orc.topk_select(Wh, hr, 5))
+
+
+@pytest.mark.parametrize("out,n,dtype,alpha,beta", [(33, 4096, "bf16", 0.125, 0.125), (9, 1531, "bf16", 0.125, 0.125),
+                                                    (16, 1000, "f32", 0.3, 0.05), (5, 7, "f32", 1.0, 1.0)])
+def test_ewma_trace_matches_oracle(orc, gpu, out, n, dtype, alpha, beta):
+    """est / dev after every weight (the two curves of the paper's tracking figure) against the oracle's
+    sequential fp32 walk and its fp64 walk: 1e-5 relative to the larger of the value and the row's mean
+    score (dev passes through zero where a score meets est)."""
+    import torch
+    from paper_2501_16376_amd import binding as b
+    say(f"[case] ewma_trace out={out} in={n} {dtype} alpha={alpha} beta={beta}")
+    Wh, hr, W, hr_dev = _inputs(orc, gpu, out, n, 256, seed=3 * out + n, dtype=dtype)
+    est = torch.full((out, n), float("nan"), dtype=torch.float32, device=gpu)
+    dev = torch.full((out, n), float("nan"), dtype=torch.float32, device=gpu)
+    b.swiftprune_ewma_trace(W, hr_dev, est, dev, alpha=alpha, beta=beta)
+    only_dev = torch.full((out, n), float("nan"), dtype=torch.float32, device=gpu)
+    b.swiftprune_ewma_trace(W, hr_dev, None, only_dev, alpha=alpha, beta=beta)
+    torch.cuda.synchronize()
+    est, dev = est.cpu().numpy(), dev.cpu().numpy()
+    assert np.array_equal(dev, only_dev.cpu().numpy())
+    L32 = orc.score(Wh, hr)
+    L64 = orc.score(Wh, hr.astype(np.float64), precision="f64")
+    for r in range(out):
+        _, e32, d32 = orc.ewma_row(L32[r], alpha, beta, 0.0)
+        _, e64, d64 = orc.ewma_row(L64[r], alpha, beta, 0.0, precision="f64")
+        floor = float(np.mean(L64[r]))
+        for got, ref in ((est[r], e32), (dev[r], d32), (est[r], e64), (dev[r], d64)):
+            err = np.abs(got.astype(np.float64) - ref) / np.maximum(np.abs(ref), floor)
+            assert err.max() <= 1e-5, (r, int(err.argmax()), float(err.max()))
