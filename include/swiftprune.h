@@ -108,6 +108,10 @@ int swiftprune_layer_stats(const void *X, int64_t tokens, int64_t in, int64_t ld
  * Default (scan) path: est/dev are evaluated as wavefront-wide linear-recurrence
  * scans; they differ from a sequential fp32 walk by a few ulp, so a decision
  * can differ only where L is within rounding of its threshold.
+ * Scores are assumed finite and inside fp32's normal range: a NaN or infinite
+ * score (a non-finite weight, or w*w overflowing) enters est and dev, after
+ * which the decisions of the rest of that row are unspecified; other rows are
+ * not affected.  No error is reported for it.
  */
 int swiftprune_score_select(const void *W, int64_t out, int64_t in, int64_t ldw, sp_dtype dt,
                             const float *hr, float sparsity, const sp_ewma_params *params,
