@@ -148,8 +148,8 @@ int swiftprune_calibrate_la(const void *W, int64_t out, int64_t in, int64_t ldw,
                             float *la, float *achieved, void *hip_stream);
 
 /*
- * Exact comparator (Sec. 3.1: "sort the L values of all weights and eliminate those with the smallest
- * L values" - the O(n log n) rule the EWMA walk replaces).  In every row the k smallest scores are
+ * Exact comparator (Sec. 3.1: order a row's scores and drop the lowest ones - the O(n log n) rule
+ * the EWMA walk replaces).  In every row the k smallest scores are
  * pruned, equal scores in index order; k = k_per_row[r] when k_per_row != NULL (device, int32[out]),
  * else k_uniform; k is clamped to [0, in].  Implemented as a per-row radix select, no sort.
  * keep_mask as above; flags: SP_APPLY_INPLACE.  NaN scores rank above every number.
@@ -164,7 +164,9 @@ int swiftprune_topk_select(const void *W, int64_t out, int64_t in, int64_t ldw, 
  * among equal scores the lower index is pruned first.  Supported: m_group in
  * {4, 8, 16}, 0 < n_keep < m_group, in % m_group == 0 (else SP_EINVAL).
  * Arguments as for swiftprune_score_select; flags: SP_APPLY_INPLACE.
- * Deterministic and order-free: with equal hr the mask is unique.
+ * Deterministic and order-free: with equal hr the mask is unique.  Scores are
+ * assumed not to be NaN: a group that holds one is not guaranteed to keep
+ * exactly n_keep entries.
  */
 int swiftprune_nm_select(const void *W, int64_t out, int64_t in, int64_t ldw, sp_dtype dt,
                          const float *hr, int n_keep, int m_group,

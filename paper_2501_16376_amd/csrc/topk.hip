@@ -1,5 +1,5 @@
-// Exact per-row selection of the k smallest scores - the "sort the L values and
-// eliminate the smallest" rule of Sec. 3.1 that the EWMA walk replaces - as a
+// Exact per-row selection of the k smallest scores - the order-and-drop-the-
+// lowest rule of Sec. 3.1 that the EWMA walk replaces - as a
 // comparator on the GPU, without a sort: one workgroup per row runs a 4-pass
 // radix select (8 bits per pass, LDS histogram) on the order-preserving bit
 // pattern of the non-negative fp32 scores, then prunes everything below the
