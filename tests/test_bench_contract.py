@@ -28,7 +28,7 @@ def test_committed_traffic_is_tied_to_the_kernel_source():
 
 
 def test_workload_byte_accounting():
-    """Algorithmic bytes of the 8B-shaped model as the design doc states them (681.6 GB with one statistics
+    """Algorithmic bytes of the 8B-shaped model from the layer shapes (681.6 GB with one statistics
     pass per linear layer, 475.5 GB with shared statistics)."""
     sys.path.insert(0, ROOT)
     from paper_2501_16376_amd import synth
