@@ -8,7 +8,7 @@ rows = st.lists(st.floats(min_value=2.0 ** -20, max_value=2.0 ** 20, allow_nan=F
 alphas = st.sampled_from([0.125, 0.25, 0.5, 0.3, 0.9, 1.0, 0.01])
 
 
-@settings(max_examples=150, deadline=None)
+@settings(max_examples=150, deadline=None, derandomize=True, database=None)
 @given(L=rows, alpha=alphas, beta=alphas, la=st.floats(min_value=-4, max_value=4, allow_nan=False))
 def test_walk_invariants(orc, L, alpha, beta, la):
     L = np.asarray(L, dtype=np.float64)
@@ -26,7 +26,7 @@ def test_walk_invariants(orc, L, alpha, beta, la):
     assert not np.any(p3.astype(bool) & ~prune.astype(bool))
 
 
-@settings(max_examples=100, deadline=None)
+@settings(max_examples=100, deadline=None, derandomize=True, database=None)
 @given(data=st.data())
 def test_nm_invariants(orc, data):
     m = data.draw(st.sampled_from([4, 8, 16]))
