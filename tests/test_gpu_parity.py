@@ -445,3 +445,59 @@ def test_full_size_gate_70b(orc, gpu):
 
 def test_full_size_down_70b(orc, gpu):
     _full_size_layer(orc, gpu, 8192, 28672, seed=1000, las=(0.5, -0.2))
+
+
+def test_matrix_beyond_4g_elements(orc, gpu):
+    """Index arithmetic past 2^32 elements: a 66000 x 65536 bf16 matrix (4.3e9 weights; row 65536 starts at
+    element 2^32 exactly).  Rows are independent, so rows on both sides of the boundary are checked
+    against the oracle one by one: EWMA (strict order and scan), 2:4, and the in-place apply."""
+    import torch
+    from paper_2501_16376_amd import binding as b, synth
+    from gpu_util import to_device, check_ewma_mask, mask_to_host
+    out, n = 66000, 65536
+    say(f"[case] {out} x {n} bf16: generating")
+    g = torch.Generator(device=gpu)
+    g.manual_seed(4242)
+    W = torch.empty((out, n), device=gpu, dtype=torch.bfloat16)
+    buf = torch.empty((6000, n), device=gpu, dtype=torch.float32)
+    for r0 in range(0, out, 6000):
+        buf.normal_(0.0, synth.W_STD, generator=g)
+        W[r0:r0 + 6000].copy_(buf[:min(6000, out - r0)])
+    del buf
+    rng = np.random.default_rng(7)
+    hr = (0.5 / (1.0 - rng.uniform(0.0, 0.02, n))).astype(np.float32)
+    hr_dev = to_device(hr, gpu)
+    rows = [0, 1, 32767, 32768, 65535, 65536, 65537, out - 1]
+    Wh = synth.torch_to_host_bits(W[rows])
+    words = n // 32
+    mask = torch.empty((out, words), dtype=torch.int32, device=gpu)
+    cnt = torch.empty(out, dtype=torch.int32, device=gpu)
+
+    say("[case] strict-order selection")
+    b.swiftprune_score_select(W, hr_dev, mask, la=0.5, row_pruned=cnt, flags=b.SP_SEQUENTIAL_ORDER)
+    torch.cuda.synchronize()
+    mask_o, cnt_o, _ = orc.ewma_select(Wh, hr, A, B, 0.5)
+    assert np.array_equal(mask_to_host(mask[rows]), mask_o)
+    assert np.array_equal(cnt[rows].cpu().numpy(), cnt_o)
+
+    say("[case] 2:4 selection")
+    b.swiftprune_nm_select(W, hr_dev, 2, 4, mask)
+    torch.cuda.synchronize()
+    nm_o, _ = orc.nm_select(Wh, hr, 2, 4)
+    assert np.array_equal(mask_to_host(mask[rows]), nm_o)
+    say("[case] apply of the 2:4 mask on a copy of the matrix")
+    W24 = W.clone()
+    b.swiftprune_apply(W24, mask)
+    torch.cuda.synchronize()
+    assert np.array_equal(synth.torch_to_host_bits(W24[rows]), orc.apply(Wh.copy(), nm_o))
+    del W24
+
+    say("[case] scan selection fused with apply")
+    b.swiftprune_score_select(W, hr_dev, mask, la=0.5, row_pruned=cnt, flags=b.SP_APPLY_INPLACE)
+    torch.cuda.synchronize()
+    m_scan = mask_to_host(mask[rows])
+    t = check_ewma_mask(orc, Wh, hr, A, B, 0.5, m_scan, cnt[rows].cpu().numpy())
+    say(f"[case] scan vs oracle on {len(rows)} rows: {t} tolerated differences")
+    assert np.array_equal(synth.torch_to_host_bits(W[rows]), orc.apply(Wh.copy(), m_scan))
+    total = int(cnt.to(torch.int64).sum().item())
+    assert 0.45 < total / (out * n) < 0.60, total / (out * n)
