@@ -2,7 +2,8 @@
 
 Loads ``oracle/liboracle.so`` (built from ``swiftprune_oracle.c`` by
 :func:`build`) and exposes its functions on numpy arrays.  bf16 tensors are
-numpy ``uint16`` arrays holding the raw bits; fp32 tensors are ``float32``.
+numpy ``uint16`` arrays holding the raw bits; fp32 tensors are ``float32``,
+IEEE half tensors ``float16``.
 
 Only the tests, the smoke check and the CPU-baseline leg of the benchmark may
 import this package.  It imports nothing from the HIP package.
@@ -19,7 +20,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "swiftprune_oracle.c")
 _LIB = os.path.join(_HERE, "liboracle.so")
 
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 
 CFLAGS = ["-O2", "-ffp-contract=off", "-fno-fast-math", "-std=c11", "-Wall", "-Wextra",
           "-shared", "-fPIC"]
@@ -93,7 +94,9 @@ def _dtype_code(a: np.ndarray) -> int:
         return BF16
     if a.dtype == np.float32:
         return F32
-    raise TypeError(f"tensor must be float32 or uint16 (bf16 bits), got {a.dtype}")
+    if a.dtype == np.float16:
+        return F16
+    raise TypeError(f"tensor must be float32, float16 or uint16 (bf16 bits), got {a.dtype}")
 
 
 def _mat(a: np.ndarray):

@@ -30,7 +30,10 @@
 #include <stdlib.h>
 #include <string.h>
 
-enum { ORC_F32 = 0, ORC_BF16 = 1 };
+enum { ORC_F32 = 0, ORC_BF16 = 1, ORC_F16 = 2 };
+
+/* bf16 and IEEE binary16 are both stored in 16 bits. */
+static inline int is_16bit(int dt) { return dt != ORC_F32; }
 
 /* bf16 is the upper half of an IEEE binary32. */
 static inline float bf16_to_f32(uint16_t b)
@@ -41,10 +44,34 @@ static inline float bf16_to_f32(uint16_t b)
     return f;
 }
 
+/* IEEE 754 binary16: 1 sign, 5 exponent (bias 15), 10 fraction bits.  Every
+ * binary16 value is exactly representable in binary32. */
+static inline float f16_to_f32(uint16_t h)
+{
+    const uint32_t sign = (uint32_t)(h & 0x8000u) << 16;
+    const uint32_t e = (h >> 10) & 0x1fu;
+    const uint32_t m = h & 0x3ffu;
+    uint32_t u;
+    float f;
+    if (e == 0) {                       /* zero or subnormal: m * 2^-24 */
+        f = (float)m * 0x1p-24f;
+        memcpy(&u, &f, sizeof u);
+        u |= sign;
+    } else if (e == 31) {               /* infinity or NaN */
+        u = sign | 0x7f800000u | (m << 13);
+    } else {                            /* normal: rebias 15 -> 127 */
+        u = sign | ((e + 112u) << 23) | (m << 13);
+    }
+    memcpy(&f, &u, sizeof f);
+    return f;
+}
+
 static inline float load_elem(const void *base, int64_t idx, int dt)
 {
     if (dt == ORC_BF16)
         return bf16_to_f32(((const uint16_t *)base)[idx]);
+    if (dt == ORC_F16)
+        return f16_to_f32(((const uint16_t *)base)[idx]);
     return ((const float *)base)[idx];
 }
 
@@ -302,7 +329,7 @@ void oracle_compact_nm(const void *W, int64_t out, int64_t in, int64_t ldw, int 
                 int64_t q = g * m_group + i;
                 if (!((keep_mask[r * words + (q >> 5)] >> (q & 31)) & 1u)) continue;
                 int64_t f = g * n_keep + j;
-                if (dt == ORC_BF16)
+                if (is_16bit(dt))
                     ((uint16_t *)values)[r * per_row + f] = ((const uint16_t *)W)[r * ldw + q];
                 else
                     ((uint32_t *)values)[r * per_row + f] = ((const uint32_t *)W)[r * ldw + q];
@@ -311,7 +338,7 @@ void oracle_compact_nm(const void *W, int64_t out, int64_t in, int64_t ldw, int 
             }
             for (; j < n_keep; ++j) {
                 int64_t f = g * n_keep + j;
-                if (dt == ORC_BF16) ((uint16_t *)values)[r * per_row + f] = 0;
+                if (is_16bit(dt)) ((uint16_t *)values)[r * per_row + f] = 0;
                 else ((uint32_t *)values)[r * per_row + f] = 0u;
             }
         }
@@ -327,7 +354,7 @@ void oracle_expand_nm(const void *values, const uint32_t *meta, int64_t out, int
     const int64_t meta_words = (per_row * b + 31) / 32;
     for (int64_t r = 0; r < out; ++r) {
         for (int64_t q = 0; q < in; ++q) {
-            if (dt == ORC_BF16) ((uint16_t *)W_out)[r * in + q] = 0;
+            if (is_16bit(dt)) ((uint16_t *)W_out)[r * in + q] = 0;
             else ((uint32_t *)W_out)[r * in + q] = 0u;
         }
         for (int64_t f = 0; f < per_row; ++f) {
@@ -335,7 +362,7 @@ void oracle_expand_nm(const void *values, const uint32_t *meta, int64_t out, int
             int64_t q = f / n_keep * m_group + pos;
             /* the output is already +0 everywhere: only non-zero bit patterns are placed, so a
                padding entry (+0 at position 0) can never overwrite a stored value */
-            if (dt == ORC_BF16) {
+            if (is_16bit(dt)) {
                 uint16_t v = ((const uint16_t *)values)[r * per_row + f];
                 if (v != 0) ((uint16_t *)W_out)[r * in + q] = v;
             } else {
@@ -359,7 +386,7 @@ void oracle_apply(void *W, int64_t out, int64_t in, int64_t ldw, int dt,
         for (int64_t q = 0; q < in; ++q) {
             int keep = (keep_mask[r * words + (q >> 5)] >> (q & 31)) & 1u;
             if (keep) continue;
-            if (dt == ORC_BF16)
+            if (is_16bit(dt))
                 ((uint16_t *)W)[r * ldw + q] = 0;
             else
                 ((float *)W)[r * ldw + q] = 0.0f;

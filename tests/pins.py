@@ -483,7 +483,50 @@ def pin_compact_nm(orc, L=None):
     assert np.array_equal(orc.expand_nm(vals, meta, 8, 2, 4, L=L), [[0, 11, 0, 0, 0, 0, 0, 0]])
 
 
-ALL_PINS = [pin_topk_is_library_sort, pin_compact_nm, pin_tracks_mean_and_deviation, pin_worked_rows, pin_closed_form, pin_constant_row, pin_first_two_elements,
+def pin_binary16_storage(orc, L=None):
+    """IEEE binary16 storage (IEEE 754-2008 Sec. 3.6): the oracle's decoder against numpy's float16 for
+    all 65536 bit patterns (through the sum of squares of a one-token activation matrix, which is exact
+    in double), and every step on a float16 matrix against the same values widened to float32."""
+    bits = np.arange(65536, dtype=np.uint16)
+    X = bits.view(np.float16).reshape(1, -1)
+    acc = orc.stats_accumulate(X, None, L=L)
+    with np.errstate(invalid="ignore", over="ignore"):
+        ref = X[0].astype(np.float64) ** 2
+    nan = np.isnan(ref)
+    assert np.array_equal(np.isnan(acc), nan)
+    assert np.array_equal(acc[~nan], ref[~nan])
+    # subnormals, the largest finite value and one ordinary value by hand
+    hand = np.array([0x0001, 0x03ff, 0x0400, 0x7bff, 0x3555, 0xc000], dtype=np.uint16).view(np.float16).reshape(1, -1)
+    want = [2.0 ** -24, 1023 * 2.0 ** -24, 2.0 ** -14, 65504.0, (1 + 0x155 / 1024) * 0.25, -2.0]
+    assert np.array_equal(orc.stats_accumulate(hand, None, L=L), np.array(want) ** 2)
+
+    rng = _rng(16)
+    out, n = 6, 96
+    W16 = rng.normal(0, 0.02, size=(out, n)).astype(np.float16)
+    W16[0, :4] = np.array([6.0e-8, -6.1e-5, 0.0, 1.5], dtype=np.float16)      # subnormal, smallest normal, zero, large
+    W32 = W16.astype(np.float32)
+    hr = (0.5 / (1.0 - rng.uniform(0, 0.3, n))).astype(np.float32)
+    assert np.array_equal(orc.score(W16, hr, L=L), orc.score(W32, hr, L=L))
+    m16, c16, _ = orc.ewma_select(W16, hr, 0.125, 0.125, 0.2, L=L)
+    m32, c32, _ = orc.ewma_select(W32, hr, 0.125, 0.125, 0.2, L=L)
+    assert np.array_equal(m16, m32) and np.array_equal(c16, c32)
+    for nk, m in ((2, 4), (4, 8)):
+        k16, _ = orc.nm_select(W16, hr, nk, m, L=L)
+        k32, _ = orc.nm_select(W32, hr, nk, m, L=L)
+        assert np.array_equal(k16, k32)
+        a16 = orc.apply(W16.copy(), k16, L=L)
+        assert a16.dtype == np.float16
+        assert np.array_equal(a16.astype(np.float32), orc.apply(W32.copy(), k32, L=L))
+        kept = orc.unpack_mask(k16, n)
+        assert np.array_equal(a16.view(np.uint16)[kept], W16.view(np.uint16)[kept])       # kept: bit for bit
+        assert np.all(a16.view(np.uint16)[~kept] == 0)                                    # pruned: +0
+        vals, meta = orc.compact_nm(W16, k16, nk, m, L=L)
+        assert vals.dtype == np.float16
+        assert np.array_equal(orc.expand_nm(vals, meta, n, nk, m, L=L).view(np.uint16), a16.view(np.uint16))
+    assert np.array_equal(orc.topk_select(W16, hr, 40, L=L), orc.topk_select(W32, hr, 40, L=L))
+
+
+ALL_PINS = [pin_binary16_storage, pin_topk_is_library_sort, pin_compact_nm, pin_tracks_mean_and_deviation, pin_worked_rows, pin_closed_form, pin_constant_row, pin_first_two_elements,
             pin_monotone_in_la, pin_step_response, pin_stats_library_sum, pin_inverse_identity,
             pin_float_factor_matches_double, pin_select_metamorphic,
             pin_uniform_energy_reduces_to_magnitude, pin_nm_invariants,

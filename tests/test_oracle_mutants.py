@@ -37,6 +37,10 @@ MUTANTS = [
      "float den = 1.0f + rho;\n        if (!(den > 0.0f))\n            den = FLT_EPSILON;\n        hr[q] = 0.5f / den;"),
     ("factor_f64_no_half", "swiftprune_oracle.c", "hr[q] = 0.5 / den;", "hr[q] = 1.0 / den;"),
     ("S_is_mean", "swiftprune_oracle.c", "*S = (float)s;", "*S = (float)(s / (double)in);"),
+    ("f16_wrong_rebias", "swiftprune_oracle.c", "((e + 112u) << 23)", "((e + 127u) << 23)"),
+    ("f16_fraction_shift", "swiftprune_oracle.c", "| (m << 13);\n    }\n    memcpy(&f, &u, sizeof f);", "| (m << 12);\n    }\n    memcpy(&f, &u, sizeof f);"),
+    ("f16_subnormal_scale", "swiftprune_oracle.c", "(float)m * 0x1p-24f", "(float)m * 0x1p-25f"),
+    ("f16_read_as_bf16", "swiftprune_oracle.c", "return f16_to_f32(((const uint16_t *)base)[idx]);", "return bf16_to_f32(((const uint16_t *)base)[idx]);"),
     ("bf16_low_half", "swiftprune_oracle.c", "uint32_t u = (uint32_t)b << 16;", "uint32_t u = (uint32_t)b;"),
     ("literal_never_updates_S", "swiftprune_oracle.c", "S_r = S_new;", ""),
     ("topk_descending", "swiftprune_oracle.c", "if (x->score < y->score) return -1;\n    if (x->score > y->score) return 1;",
