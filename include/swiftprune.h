@@ -34,7 +34,9 @@
 extern "C" {
 #endif
 
-typedef enum { SP_F32 = 0, SP_BF16 = 1 } sp_dtype;
+/* storage type of X and W: IEEE binary32, bfloat16, IEEE binary16.  All arithmetic is fp32 (fp64 inside the
+ * statistics sums) whatever the storage; a 16-bit element widens to fp32 exactly. */
+typedef enum { SP_F32 = 0, SP_BF16 = 1, SP_F16 = 2 } sp_dtype;
 
 typedef enum {
     SP_OK = 0,

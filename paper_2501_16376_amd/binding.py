@@ -15,7 +15,7 @@ import os
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libswiftprune.so")
 
-SP_F32, SP_BF16 = 0, 1
+SP_F32, SP_BF16, SP_F16 = 0, 1, 2
 SP_OK, SP_EINVAL, SP_ENOSPC, SP_EHIP, SP_ERANGE = 0, -1, -2, -3, -4
 SP_SEQUENTIAL_ORDER, SP_APPLY_INPLACE = 1, 2
 
@@ -92,7 +92,9 @@ def _dtype_code(t) -> int:
         return SP_BF16
     if t.dtype == torch.float32:
         return SP_F32
-    raise TypeError(f"tensor must be bfloat16 or float32, got {t.dtype}")
+    if t.dtype == torch.float16:
+        return SP_F16
+    raise TypeError(f"tensor must be bfloat16, float16 or float32, got {t.dtype}")
 
 
 def _matrix(t):

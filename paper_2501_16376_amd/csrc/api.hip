@@ -9,8 +9,8 @@
 namespace {
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
-inline int64_t elem_size(int dt) { return dt == SP_BF16 ? 2 : 4; }
-inline bool dtype_ok(int dt) { return dt == SP_F32 || dt == SP_BF16; }
+inline int64_t elem_size(int dt) { return dt == SP_F32 ? 4 : 2; }
+inline bool dtype_ok(int dt) { return dt == SP_F32 || dt == SP_BF16 || dt == SP_F16; }
 
 // the 16-byte-vector path of the statistics kernel
 inline bool stats_vec_ok(const void* X, int64_t in, int64_t ldx, int dt) {
@@ -67,7 +67,7 @@ int swiftprune_la_for_sparsity(float sparsity, float* la) {
 size_t swiftprune_stats_workspace_bytes(int64_t tokens, int64_t in) {
     if (tokens <= 0 || in <= 0) return 0;
     size_t bytes = 0;
-    for (int dt = 0; dt < 2; ++dt)
+    for (int dt = 0; dt < 3; ++dt)
         for (int vec = 0; vec < 2; ++vec) {
             const size_t b = sp::stats_workspace_bytes(sp::make_stats_plan(tokens, in, dt, vec != 0));
             if (b > bytes) bytes = b;

@@ -67,14 +67,12 @@ hipError_t launch_count_pruned(const void* W, int64_t out, int64_t in, int64_t l
     hipLaunchKernelGGL(zero_counts_kernel, dim3(1), dim3(64), 0, stream, counts, n_la);
     const unsigned grid = (unsigned)((out + kScanWaves - 1) / kScanWaves);
     const dim3 block(kScanWaves * kWave);
-    if (dt == kBF16) {
-        if (vec) hipLaunchKernelGGL((ewma_count_kernel<kBF16, true>), dim3(grid), block, 0, stream, W, out, in, ldw, hr, c, cand, counts);
-        else hipLaunchKernelGGL((ewma_count_kernel<kBF16, false>), dim3(grid), block, 0, stream, W, out, in, ldw, hr, c, cand, counts);
-    } else {
-        if (vec) hipLaunchKernelGGL((ewma_count_kernel<kF32, true>), dim3(grid), block, 0, stream, W, out, in, ldw, hr, c, cand, counts);
-        else hipLaunchKernelGGL((ewma_count_kernel<kF32, false>), dim3(grid), block, 0, stream, W, out, in, ldw, hr, c, cand, counts);
-    }
-    return hipGetLastError();
+    return with_dtype(dt, [&](auto tag) {
+        constexpr int DT = decltype(tag)::value;
+        if (vec) hipLaunchKernelGGL((ewma_count_kernel<DT, true>), dim3(grid), block, 0, stream, W, out, in, ldw, hr, c, cand, counts);
+        else hipLaunchKernelGGL((ewma_count_kernel<DT, false>), dim3(grid), block, 0, stream, W, out, in, ldw, hr, c, cand, counts);
+        return hipGetLastError();
+    });
 }
 
 // Host-driven bracketing search.  Each pass: 16 equally spaced candidates over [lo, hi], one counting

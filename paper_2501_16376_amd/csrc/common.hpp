@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace sp {
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
@@ -12,10 +14,39 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kWave = 64;
 constexpr int kF32 = 0;
 constexpr int kBF16 = 1;
+constexpr int kF16 = 2;   // IEEE binary16
 
-// ---- bf16 <-> fp32 (bf16 is the upper half of an IEEE binary32) ----
+// ---- bf16 -> fp32 (bf16 is the upper half of an IEEE binary32) ----
 __device__ __forceinline__ float bf16lo(uint32_t pair) { return __uint_as_float(pair << 16); }
 __device__ __forceinline__ float bf16hi(uint32_t pair) { return __uint_as_float(pair & 0xffff0000u); }
+// ---- binary16 -> fp32 (exact; one conversion instruction, subnormals included) ----
+__device__ __forceinline__ float f16bits(uint16_t h) { return (float)__builtin_bit_cast(_Float16, h); }
+__device__ __forceinline__ float f16lo(uint32_t pair) { return f16bits((uint16_t)(pair & 0xffffu)); }
+__device__ __forceinline__ float f16hi(uint32_t pair) { return f16bits((uint16_t)(pair >> 16)); }
+
+// Host side: calls f(std::integral_constant<int, DT>{}) with the storage type as a compile-time constant.
+template <class F>
+inline hipError_t with_dtype(int dt, F&& f) {
+    switch (dt) {
+        case kF32: return f(std::integral_constant<int, kF32>{});
+        case kBF16: return f(std::integral_constant<int, kBF16>{});
+        case kF16: return f(std::integral_constant<int, kF16>{});
+        default: return hipErrorInvalidValue;
+    }
+}
+
+// One stored element as fp32 / set to +0 (element-wise paths).
+template <int DT>
+__device__ __forceinline__ float load_scalar(const void* p, int64_t idx) {
+    if (DT == kBF16) return __uint_as_float((uint32_t)static_cast<const uint16_t*>(p)[idx] << 16);
+    if (DT == kF16) return f16bits(static_cast<const uint16_t*>(p)[idx]);
+    return static_cast<const float*>(p)[idx];
+}
+template <int DT>
+__device__ __forceinline__ void store_zero(void* p, int64_t idx) {
+    if (DT == kF32) static_cast<float*>(p)[idx] = 0.0f;
+    else static_cast<uint16_t*>(p)[idx] = 0;
+}
 
 // ---- DPP moves; lanes without a valid source (or masked off) receive 0 ----
 template <int CTRL, int ROW_MASK = 0xf>
@@ -50,8 +81,8 @@ __device__ __forceinline__ uint32_t quad_gather_bytes(uint32_t byte, int lane) {
 template <int DT>
 struct Chunk8;
 
-template <>
-struct Chunk8<kBF16> {
+// storage side of the two 16-bit types: four 32-bit words holding eight elements
+struct Chunk8Halves {
     uint32_t raw[4];
     // 16-byte aligned vector load; weights are streamed once, so the load is non-temporal
     __device__ __forceinline__ void load_vec(const void* base, int64_t elem_off) {
@@ -70,9 +101,6 @@ struct Chunk8<kBF16> {
         }
     }
     __device__ __forceinline__ void zero() { raw[0] = raw[1] = raw[2] = raw[3] = 0u; }
-    __device__ __forceinline__ float get(int k) const {
-        return (k & 1) ? bf16hi(raw[k >> 1]) : bf16lo(raw[k >> 1]);
-    }
     // zero the elements whose keep bit is 0
     __device__ __forceinline__ void apply(uint32_t keep_byte) {
 #pragma unroll
@@ -105,6 +133,20 @@ struct Chunk8<kBF16> {
 #pragma unroll
         for (int k = 0; k < 8; ++k)
             if (k < valid) p[k] = (uint16_t)((k & 1) ? (raw[k >> 1] >> 16) : (raw[k >> 1] & 0xffffu));
+    }
+};
+
+template <>
+struct Chunk8<kBF16> : Chunk8Halves {
+    __device__ __forceinline__ float get(int k) const {
+        return (k & 1) ? bf16hi(raw[k >> 1]) : bf16lo(raw[k >> 1]);
+    }
+};
+
+template <>
+struct Chunk8<kF16> : Chunk8Halves {
+    __device__ __forceinline__ float get(int k) const {
+        return (k & 1) ? f16hi(raw[k >> 1]) : f16lo(raw[k >> 1]);
     }
 };
 

@@ -17,12 +17,12 @@ __host__ __device__ inline int nm_index_bits(int m_group) { return m_group == 4 
 
 template <int DT>
 __device__ __forceinline__ uint32_t load_raw(const void* p, int64_t idx) {
-    if (DT == kBF16) return static_cast<const uint16_t*>(p)[idx];
+    if (DT != kF32) return static_cast<const uint16_t*>(p)[idx];   // bf16 and fp16: 16-bit storage
     return static_cast<const uint32_t*>(p)[idx];
 }
 template <int DT>
 __device__ __forceinline__ void store_raw(void* p, int64_t idx, uint32_t v) {
-    if (DT == kBF16) static_cast<uint16_t*>(p)[idx] = (uint16_t)v;
+    if (DT != kF32) static_cast<uint16_t*>(p)[idx] = (uint16_t)v;
     else static_cast<uint32_t*>(p)[idx] = v;
 }
 
@@ -114,13 +114,12 @@ hipError_t launch_compact_nm(const void* W, int64_t out, int64_t in, int64_t ldw
     if ((int64_t)chunk_blocks * out > 0x7fffffff) return hipErrorInvalidValue;
     dim3 grid((unsigned)(chunk_blocks * out));
     const int64_t mw = nm_meta_words(in, n_keep, m_group);
-    if (dt == kBF16)
-        hipLaunchKernelGGL(compact_nm_kernel<kBF16>, grid, dim3(64), 0, stream, W, in, ldw, keep_mask, n_keep,
-                           m_group, values, meta, mw, chunk_blocks);
-    else
-        hipLaunchKernelGGL(compact_nm_kernel<kF32>, grid, dim3(64), 0, stream, W, in, ldw, keep_mask, n_keep,
-                           m_group, values, meta, mw, chunk_blocks);
-    return hipGetLastError();
+    return with_dtype(dt, [&](auto tag) {
+        constexpr int DT = decltype(tag)::value;
+        hipLaunchKernelGGL(compact_nm_kernel<DT>, grid, dim3(64), 0, stream, W, in, ldw, keep_mask, n_keep, m_group,
+                           values, meta, mw, chunk_blocks);
+        return hipGetLastError();
+    });
 }
 
 hipError_t launch_expand_nm(const void* values, const uint32_t* meta, int64_t out, int64_t in, int dt,
@@ -130,13 +129,12 @@ hipError_t launch_expand_nm(const void* values, const uint32_t* meta, int64_t ou
     if ((int64_t)chunk_blocks * out > 0x7fffffff) return hipErrorInvalidValue;
     dim3 grid((unsigned)(chunk_blocks * out));
     const int64_t mw = nm_meta_words(in, n_keep, m_group);
-    if (dt == kBF16)
-        hipLaunchKernelGGL(expand_nm_kernel<kBF16>, grid, dim3(64), 0, stream, values, meta, in, n_keep, m_group,
-                           mw, W_out, ldw, chunk_blocks);
-    else
-        hipLaunchKernelGGL(expand_nm_kernel<kF32>, grid, dim3(64), 0, stream, values, meta, in, n_keep, m_group,
-                           mw, W_out, ldw, chunk_blocks);
-    return hipGetLastError();
+    return with_dtype(dt, [&](auto tag) {
+        constexpr int DT = decltype(tag)::value;
+        hipLaunchKernelGGL(expand_nm_kernel<DT>, grid, dim3(64), 0, stream, values, meta, in, n_keep, m_group, mw,
+                           W_out, ldw, chunk_blocks);
+        return hipGetLastError();
+    });
 }
 
 }  // namespace sp

@@ -181,11 +181,11 @@ static hipError_t launch_nm_t(const void* W, int64_t out, int64_t in, int64_t ld
 hipError_t launch_nm_select(const void* W, int64_t out, int64_t in, int64_t ldw, int dt, bool vec,
                             const float* hr, int n_keep, int m_group, uint32_t* keep_mask,
                             float* scores, bool apply, hipStream_t stream) {
-    if (dt == kBF16)
-        return vec ? launch_nm_t<kBF16, true>(W, out, in, ldw, hr, n_keep, m_group, keep_mask, scores, apply, stream)
-                   : launch_nm_t<kBF16, false>(W, out, in, ldw, hr, n_keep, m_group, keep_mask, scores, apply, stream);
-    return vec ? launch_nm_t<kF32, true>(W, out, in, ldw, hr, n_keep, m_group, keep_mask, scores, apply, stream)
-               : launch_nm_t<kF32, false>(W, out, in, ldw, hr, n_keep, m_group, keep_mask, scores, apply, stream);
+    return with_dtype(dt, [&](auto tag) {
+        constexpr int DT = decltype(tag)::value;
+        return vec ? launch_nm_t<DT, true>(W, out, in, ldw, hr, n_keep, m_group, keep_mask, scores, apply, stream)
+                   : launch_nm_t<DT, false>(W, out, in, ldw, hr, n_keep, m_group, keep_mask, scores, apply, stream);
+    });
 }
 
 hipError_t launch_apply(void* W, int64_t out, int64_t in, int64_t ldw, int dt, bool vec,
@@ -195,14 +195,12 @@ hipError_t launch_apply(void* W, int64_t out, int64_t in, int64_t ldw, int dt, b
     const int64_t tiles = (int64_t)col_tiles * ((out + kRows - 1) / kRows);
     if (tiles > 0x7fffffff) return hipErrorInvalidValue;
     dim3 grid((unsigned)tiles);
-    if (dt == kBF16) {
-        if (vec) hipLaunchKernelGGL((apply_kernel<kBF16, true>), grid, dim3(kColThreads), 0, stream, W, out, in, ldw, keep_mask, col_tiles);
-        else hipLaunchKernelGGL((apply_kernel<kBF16, false>), grid, dim3(kColThreads), 0, stream, W, out, in, ldw, keep_mask, col_tiles);
-    } else {
-        if (vec) hipLaunchKernelGGL((apply_kernel<kF32, true>), grid, dim3(kColThreads), 0, stream, W, out, in, ldw, keep_mask, col_tiles);
-        else hipLaunchKernelGGL((apply_kernel<kF32, false>), grid, dim3(kColThreads), 0, stream, W, out, in, ldw, keep_mask, col_tiles);
-    }
-    return hipGetLastError();
+    return with_dtype(dt, [&](auto tag) {
+        constexpr int DT = decltype(tag)::value;
+        if (vec) hipLaunchKernelGGL((apply_kernel<DT, true>), grid, dim3(kColThreads), 0, stream, W, out, in, ldw, keep_mask, col_tiles);
+        else hipLaunchKernelGGL((apply_kernel<DT, false>), grid, dim3(kColThreads), 0, stream, W, out, in, ldw, keep_mask, col_tiles);
+        return hipGetLastError();
+    });
 }
 
 }  // namespace sp

@@ -230,22 +230,17 @@ static hipError_t launch_scan_t(const void* W, int64_t out, int64_t in, int64_t 
 hipError_t launch_ewma_scan(const void* W, int64_t out, int64_t in, int64_t ldw, int dt, bool vec,
                             const float* hr, const EwmaConsts& c, uint32_t* keep_mask,
                             int32_t* row_pruned, float* scores, bool apply, hipStream_t stream) {
-    if (vec && scores == nullptr && c.alpha < 1.0f) {
-        const unsigned grid = (unsigned)((out + kScanWaves - 1) / kScanWaves);
-        void* Wm = const_cast<void*>(W);
-        if (dt == kBF16)
-            hipLaunchKernelGGL(ewma_scan_fast_kernel<kBF16>, dim3(grid), dim3(kScanWaves * kWave), 0, stream, Wm,
-                               out, in, ldw, hr, c, keep_mask, row_pruned, apply ? 1 : 0);
-        else
-            hipLaunchKernelGGL(ewma_scan_fast_kernel<kF32>, dim3(grid), dim3(kScanWaves * kWave), 0, stream, Wm,
-                               out, in, ldw, hr, c, keep_mask, row_pruned, apply ? 1 : 0);
-        return hipGetLastError();
-    }
-    if (dt == kBF16)
-        return vec ? launch_scan_t<kBF16, true>(W, out, in, ldw, hr, c, keep_mask, row_pruned, scores, apply, stream)
-                   : launch_scan_t<kBF16, false>(W, out, in, ldw, hr, c, keep_mask, row_pruned, scores, apply, stream);
-    return vec ? launch_scan_t<kF32, true>(W, out, in, ldw, hr, c, keep_mask, row_pruned, scores, apply, stream)
-               : launch_scan_t<kF32, false>(W, out, in, ldw, hr, c, keep_mask, row_pruned, scores, apply, stream);
+    return with_dtype(dt, [&](auto tag) {
+        constexpr int DT = decltype(tag)::value;
+        if (vec && scores == nullptr && c.alpha < 1.0f) {
+            const unsigned grid = (unsigned)((out + kScanWaves - 1) / kScanWaves);
+            hipLaunchKernelGGL(ewma_scan_fast_kernel<DT>, dim3(grid), dim3(kScanWaves * kWave), 0, stream,
+                               const_cast<void*>(W), out, in, ldw, hr, c, keep_mask, row_pruned, apply ? 1 : 0);
+            return hipGetLastError();
+        }
+        return vec ? launch_scan_t<DT, true>(W, out, in, ldw, hr, c, keep_mask, row_pruned, scores, apply, stream)
+                   : launch_scan_t<DT, false>(W, out, in, ldw, hr, c, keep_mask, row_pruned, scores, apply, stream);
+    });
 }
 
 }  // namespace sp

@@ -9,18 +9,6 @@
 namespace sp {
 
 template <int DT>
-__device__ __forceinline__ float load_w(const void* W, int64_t idx) {
-    if (DT == kBF16) return __uint_as_float((uint32_t)static_cast<const uint16_t*>(W)[idx] << 16);
-    return static_cast<const float*>(W)[idx];
-}
-
-template <int DT>
-__device__ __forceinline__ void store_zero(void* W, int64_t idx) {
-    if (DT == kBF16) static_cast<uint16_t*>(W)[idx] = 0;
-    else static_cast<uint32_t*>(W)[idx] = 0u;
-}
-
-template <int DT>
 __global__ __launch_bounds__(64) void ewma_sequential_kernel(
     void* __restrict__ W, int64_t out, int64_t in, int64_t ldw, const float* __restrict__ hr,
     float alpha, float beta, float la, uint32_t* __restrict__ keep_mask,
@@ -34,7 +22,7 @@ __global__ __launch_bounds__(64) void ewma_sequential_kernel(
     int pruned = 0;
     uint32_t word = 0u;
     for (int64_t q = 0; q < in; ++q) {
-        const float w = load_w<DT>(W, row * ldw + q);
+        const float w = load_scalar<DT>(W, row * ldw + q);
         const float L = score_of(w, hr[q]);
         if (scores != nullptr) scores[row * in + q] = L;
         if (q == 0) est = L;
@@ -67,15 +55,12 @@ hipError_t launch_ewma_sequential(const void* W, int64_t out, int64_t in, int64_
                                   uint32_t* keep_mask, int32_t* row_pruned, float* scores, bool apply,
                                   hipStream_t stream) {
     const unsigned grid = (unsigned)((out + 63) / 64);
-    if (dt == kBF16)
-        hipLaunchKernelGGL(ewma_sequential_kernel<kBF16>, dim3(grid), dim3(64), 0, stream,
-                           const_cast<void*>(W), out, in, ldw, hr, alpha, beta, la, keep_mask,
-                           row_pruned, scores, apply ? 1 : 0);
-    else
-        hipLaunchKernelGGL(ewma_sequential_kernel<kF32>, dim3(grid), dim3(64), 0, stream,
-                           const_cast<void*>(W), out, in, ldw, hr, alpha, beta, la, keep_mask,
-                           row_pruned, scores, apply ? 1 : 0);
-    return hipGetLastError();
+    return with_dtype(dt, [&](auto tag) {
+        constexpr int DT = decltype(tag)::value;
+        hipLaunchKernelGGL(ewma_sequential_kernel<DT>, dim3(grid), dim3(64), 0, stream, const_cast<void*>(W), out,
+                           in, ldw, hr, alpha, beta, la, keep_mask, row_pruned, scores, apply ? 1 : 0);
+        return hipGetLastError();
+    });
 }
 
 }  // namespace sp

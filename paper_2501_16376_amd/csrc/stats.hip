@@ -4,7 +4,7 @@
 //
 // X[tokens, in] is streamed exactly once with non-temporal 16-byte loads.  The
 // columns are cut into strips of at most 256 sixteen-byte units (one unit per
-// lane of a 256-thread workgroup: 2048 bf16 or 1024 fp32 columns, contiguous in
+// lane of a 256-thread workgroup: 2048 bf16 / fp16 or 1024 fp32 columns, contiguous in
 // every row) and the tokens into batches of 4 or 8 consecutive rows that are
 // dealt round-robin to `splits` workgroups per strip, so that at any moment the
 // whole device reads one moving window of a few MB (measured 1-7 % faster than
@@ -53,6 +53,25 @@ struct XUnit<kBF16, 8> {
 };
 
 template <>
+struct XUnit<kF16, 8> {
+    u32x4 r;
+    __device__ __forceinline__ void load(const void* X, int64_t elem) {
+        r = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(X) + elem));
+    }
+    __device__ __forceinline__ void sq_add(float* a) const {
+        float v;
+        v = f16lo(r.x); a[0] = fmaf(v, v, a[0]);
+        v = f16hi(r.x); a[1] = fmaf(v, v, a[1]);
+        v = f16lo(r.y); a[2] = fmaf(v, v, a[2]);
+        v = f16hi(r.y); a[3] = fmaf(v, v, a[3]);
+        v = f16lo(r.z); a[4] = fmaf(v, v, a[4]);
+        v = f16hi(r.z); a[5] = fmaf(v, v, a[5]);
+        v = f16lo(r.w); a[6] = fmaf(v, v, a[6]);
+        v = f16hi(r.w); a[7] = fmaf(v, v, a[7]);
+    }
+};
+
+template <>
 struct XUnit<kF32, 4> {
     f32x4 r;
     __device__ __forceinline__ void load(const void* X, int64_t elem) {
@@ -71,6 +90,15 @@ struct XUnit<kBF16, 1> {
     float r;
     __device__ __forceinline__ void load(const void* X, int64_t elem) {
         r = __uint_as_float((uint32_t)__builtin_nontemporal_load(static_cast<const uint16_t*>(X) + elem) << 16);
+    }
+    __device__ __forceinline__ void sq_add(float* a) const { a[0] = fmaf(r, r, a[0]); }
+};
+
+template <>
+struct XUnit<kF16, 1> {
+    float r;
+    __device__ __forceinline__ void load(const void* X, int64_t elem) {
+        r = f16bits(__builtin_nontemporal_load(static_cast<const uint16_t*>(X) + elem));
     }
     __device__ __forceinline__ void sq_add(float* a) const { a[0] = fmaf(r, r, a[0]); }
 };
@@ -246,7 +274,7 @@ static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 StatsPlan make_stats_plan(int64_t tokens, int64_t in, int dt, bool vec) {
     StatsPlan p;
-    p.epu = vec ? (dt == kBF16 ? 8 : 4) : 1;
+    p.epu = vec ? (dt == kF32 ? 4 : 8) : 1;
     p.units = ceil_div(in, p.epu);
     p.nstrips = (int)ceil_div(p.units, kStatsThreads);
     // equal strips, rounded up to 8 units (128 bytes) so that strips start on a cache line
@@ -304,6 +332,9 @@ hipError_t launch_layer_stats(const void* X, int64_t tokens, int64_t in, int64_t
     if (dt == kBF16)
         e = vec ? launch_partial<kBF16, 8>(X, tokens, ldx, p, partials, group_sums, stream)
                 : launch_partial<kBF16, 1>(X, tokens, ldx, p, partials, group_sums, stream);
+    else if (dt == kF16)
+        e = vec ? launch_partial<kF16, 8>(X, tokens, ldx, p, partials, group_sums, stream)
+                : launch_partial<kF16, 1>(X, tokens, ldx, p, partials, group_sums, stream);
     else
         e = vec ? launch_partial<kF32, 4>(X, tokens, ldx, p, partials, group_sums, stream)
                 : launch_partial<kF32, 1>(X, tokens, ldx, p, partials, group_sums, stream);

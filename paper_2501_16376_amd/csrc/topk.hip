@@ -15,10 +15,7 @@ constexpr int kTopkThreads = 256;
 
 template <int DT>
 __device__ __forceinline__ uint32_t score_key(const void* W, int64_t idx, float factor) {
-    float w;
-    if (DT == kBF16) w = __uint_as_float((uint32_t)static_cast<const uint16_t*>(W)[idx] << 16);
-    else w = static_cast<const float*>(W)[idx];
-    const float L = score_of(w, factor);
+    const float L = score_of(load_scalar<DT>(W, idx), factor);
     // scores are >= +0 (or NaN): the bit pattern orders them; NaN sorts above +inf
     return __float_as_uint(L) & 0x7fffffffu;
 }
@@ -113,10 +110,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_select_kernel(
                 else if (key == T) prune = (tie_rank++ < remaining);
             }
             if (!prune) word |= 1u << (q & 31);
-            else if (apply) {
-                if (DT == kBF16) static_cast<uint16_t*>(W)[base + q] = 0;
-                else static_cast<uint32_t*>(W)[base + q] = 0u;
-            }
+            else if (apply) store_zero<DT>(W, base + q);
         }
         keep_mask[row * mask_words + (w0 >> 5)] = word;
     }
@@ -128,13 +122,12 @@ hipError_t launch_topk_select(const void* W, int64_t out, int64_t in, int64_t ld
     int64_t cpt = (in + kTopkThreads - 1) / kTopkThreads;
     cpt = (cpt + 31) / 32 * 32;
     void* Wm = const_cast<void*>(W);
-    if (dt == kBF16)
-        hipLaunchKernelGGL(topk_select_kernel<kBF16>, dim3((unsigned)out), dim3(kTopkThreads), 0, stream, Wm, in,
-                           ldw, hr, k_per_row, k_uniform, keep_mask, (int)cpt, apply ? 1 : 0);
-    else
-        hipLaunchKernelGGL(topk_select_kernel<kF32>, dim3((unsigned)out), dim3(kTopkThreads), 0, stream, Wm, in,
-                           ldw, hr, k_per_row, k_uniform, keep_mask, (int)cpt, apply ? 1 : 0);
-    return hipGetLastError();
+    return with_dtype(dt, [&](auto tag) {
+        constexpr int DT = decltype(tag)::value;
+        hipLaunchKernelGGL(topk_select_kernel<DT>, dim3((unsigned)out), dim3(kTopkThreads), 0, stream, Wm, in, ldw,
+                           hr, k_per_row, k_uniform, keep_mask, (int)cpt, apply ? 1 : 0);
+        return hipGetLastError();
+    });
 }
 
 }  // namespace sp

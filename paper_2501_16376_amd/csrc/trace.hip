@@ -38,11 +38,11 @@ static hipError_t launch_trace_t(const void* W, int64_t out, int64_t in, int64_t
 hipError_t launch_ewma_trace(const void* W, int64_t out, int64_t in, int64_t ldw, int dt, bool vec,
                              const float* hr, const EwmaConsts& c, float* est, float* dev,
                              hipStream_t stream) {
-    if (dt == kBF16)
-        return vec ? launch_trace_t<kBF16, true>(W, out, in, ldw, hr, c, est, dev, stream)
-                   : launch_trace_t<kBF16, false>(W, out, in, ldw, hr, c, est, dev, stream);
-    return vec ? launch_trace_t<kF32, true>(W, out, in, ldw, hr, c, est, dev, stream)
-               : launch_trace_t<kF32, false>(W, out, in, ldw, hr, c, est, dev, stream);
+    return with_dtype(dt, [&](auto tag) {
+        constexpr int DT = decltype(tag)::value;
+        return vec ? launch_trace_t<DT, true>(W, out, in, ldw, hr, c, est, dev, stream)
+                   : launch_trace_t<DT, false>(W, out, in, ldw, hr, c, est, dev, stream);
+    });
 }
 
 }  // namespace sp

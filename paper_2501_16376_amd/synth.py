@@ -64,7 +64,7 @@ def channel_scales(n_in: int, n_outlier: int, rng: np.random.Generator) -> np.nd
 
 def layer_inputs(out: int, n_in: int, tokens: int, seed: int = 0, dtype: str = "bf16",
                  n_outlier: int | None = None):
-    """(W, X) on the host.  dtype "f32" -> float32 arrays; "bf16" -> uint16 bit patterns."""
+    """(W, X) on the host.  dtype "f32" -> float32 arrays; "bf16" -> uint16 bit patterns; "f16" -> float16."""
     rng = np.random.default_rng(seed)
     if n_outlier is None:
         n_outlier = default_outliers(n_in)
@@ -75,6 +75,8 @@ def layer_inputs(out: int, n_in: int, tokens: int, seed: int = 0, dtype: str = "
         return W, X
     if dtype == "bf16":
         return f32_to_bf16_bits(W), f32_to_bf16_bits(X)
+    if dtype == "f16":
+        return W.astype(np.float16), X.astype(np.float16)
     raise ValueError(dtype)
 
 
@@ -84,6 +86,11 @@ def config1(seed: int = 0):
 
 
 # ------------------------------------------------------------------ device (torch) generator
+def _torch_dtype(dtype: str):
+    import torch
+    return {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[dtype]
+
+
 def device_weights(out: int, n_in: int, seed: int, device="cuda", dtype: str = "bf16"):
     """W on the device from a seeded device generator (torch is used for memory and RNG only)."""
     import torch
@@ -91,7 +98,7 @@ def device_weights(out: int, n_in: int, seed: int, device="cuda", dtype: str = "
     g.manual_seed(int(seed))
     W = torch.empty((out, n_in), device=device, dtype=torch.float32)
     W.normal_(0.0, W_STD, generator=g)
-    return W if dtype == "f32" else W.to(torch.bfloat16)
+    return W if dtype == "f32" else W.to(_torch_dtype(dtype))
 
 
 def device_activations(tokens: int, n_in: int, seed: int, device="cuda", dtype: str = "bf16",
@@ -104,7 +111,7 @@ def device_activations(tokens: int, n_in: int, seed: int, device="cuda", dtype: 
     s = torch.from_numpy(channel_scales(n_in, n_outlier, rng)).to(device)
     g = torch.Generator(device=device)
     g.manual_seed(int(seed) + 0x5EED)
-    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    tdt = _torch_dtype(dtype)
     X = torch.empty((tokens, n_in), device=device, dtype=tdt)
     buf = torch.empty((min(chunk_tokens, tokens), n_in), device=device, dtype=torch.float32)
     for t0 in range(0, tokens, chunk_tokens):

@@ -5,11 +5,19 @@ import numpy as np
 
 
 def to_device(a: np.ndarray, device="cuda"):
-    """numpy float32 / uint16 (bf16 bits) -> torch tensor on the GPU with the same bits."""
+    """numpy float32 / float16 / uint16 (bf16 bits) -> torch tensor on the GPU with the same bits."""
     import torch
     if a.dtype == np.uint16:
         return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).view(torch.bfloat16).to(device)
     return torch.from_numpy(np.ascontiguousarray(a)).to(device)
+
+
+def same_bits(a: np.ndarray, b: np.ndarray) -> bool:
+    """Bit-for-bit equality of two arrays of one dtype (so that -0 and +0 differ)."""
+    if a.dtype != b.dtype or a.shape != b.shape:
+        return False
+    u = {2: np.uint16, 4: np.uint32}[a.dtype.itemsize]
+    return np.array_equal(np.ascontiguousarray(a).view(u), np.ascontiguousarray(b).view(u))
 
 
 def mask_to_host(t) -> np.ndarray:

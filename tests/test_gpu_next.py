@@ -33,7 +33,7 @@ def _inputs(orc, gpu, out, n, tokens, seed, dtype="bf16"):
     return Wh, hr, to_device(Wh, gpu), to_device(hr, gpu)
 
 
-@pytest.mark.parametrize("out,n,dtype", [(200, 2048, "bf16"), (37, 1000, "bf16"), (64, 777, "f32")])
+@pytest.mark.parametrize("out,n,dtype", [(200, 2048, "bf16"), (37, 1000, "bf16"), (64, 777, "f32"), (50, 1536, "f16")])
 def test_count_pruned_matches_oracle(orc, gpu, out, n, dtype):
     """Counts for 16 (and for 3) candidate la in one pass equal the oracle's totals, up to the few
     decisions the scan path may flip at the rounding level."""
@@ -75,7 +75,7 @@ def test_calibrate_la_hits_targets(orc, gpu):
     assert not reached and la == 0.0
 
 
-@pytest.mark.parametrize("out,n,dtype", [(64, 4096, "bf16"), (9, 1000, "bf16"), (17, 333, "f32"), (3, 40000, "bf16")])
+@pytest.mark.parametrize("out,n,dtype", [(64, 4096, "bf16"), (9, 1000, "bf16"), (17, 333, "f32"), (3, 40000, "bf16"), (21, 2000, "f16")])
 def test_topk_select_matches_sort(orc, gpu, out, n, dtype):
     """Radix-select masks equal the oracle's sort-based masks bit for bit (same factor), for per-row k,
     uniform k, k = 0, k >= in, and rows full of ties."""
@@ -143,14 +143,14 @@ def test_ewma_vs_sort_overlap_at_scale(orc, gpu):
         assert overlap > 0.85
 
 
-@pytest.mark.parametrize("out,n,dtype", [(40, 4096, "bf16"), (7, 1000, "bf16"), (5, 2048, "f32")])
+@pytest.mark.parametrize("out,n,dtype", [(40, 4096, "bf16"), (7, 1000, "bf16"), (5, 2048, "f32"), (12, 1024, "f16")])
 def test_compact_and_expand_nm(orc, gpu, out, n, dtype):
     """Compact values/meta and the expanded matrix equal the oracle's, bit for bit."""
     import torch
     from paper_2501_16376_amd import binding as b, synth
-    from gpu_util import to_device, mask_to_host
+    from gpu_util import to_device, mask_to_host, same_bits
     Wh, hr, W, hr_dev = _inputs(orc, gpu, out, n, 128, seed=3 * out + n, dtype=dtype)
-    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    tdt = {"bf16": torch.bfloat16, "f32": torch.float32, "f16": torch.float16}[dtype]
     for nk, m in ((2, 4), (4, 8), (1, 4), (6, 8), (8, 16)):
         if n % m:
             continue
@@ -166,10 +166,10 @@ def test_compact_and_expand_nm(orc, gpu, out, n, dtype):
         b.swiftprune_expand_nm(vals, meta, n, nk, m, dense)
         torch.cuda.synchronize()
         v_o, m_o = orc.compact_nm(Wh, mask_to_host(mask), nk, m)
-        assert np.array_equal(synth.torch_to_host_bits(vals), v_o)
+        assert same_bits(synth.torch_to_host_bits(vals), v_o)
         assert np.array_equal(mask_to_host(meta), m_o)
-        assert np.array_equal(synth.torch_to_host_bits(dense), orc.expand_nm(v_o, m_o, n, nk, m))
-        assert np.array_equal(synth.torch_to_host_bits(dense), orc.apply(Wh.copy(), mask_to_host(mask)))
+        assert same_bits(synth.torch_to_host_bits(dense), orc.expand_nm(v_o, m_o, n, nk, m))
+        assert same_bits(synth.torch_to_host_bits(dense), orc.apply(Wh.copy(), mask_to_host(mask)))
     # a mask that is not N:M (EWMA mask): extra kept entries dropped, missing ones padded - same as the oracle
     mask = torch.empty((out, (n + 31) // 32), dtype=torch.int32, device=gpu)
     b.swiftprune_score_select(W, hr_dev, mask, la=0.5)
@@ -178,7 +178,7 @@ def test_compact_and_expand_nm(orc, gpu, out, n, dtype):
     b.swiftprune_compact_nm(W, mask, 2, 4, vals, meta)
     torch.cuda.synchronize()
     v_o, m_o = orc.compact_nm(Wh, mask_to_host(mask), 2, 4)
-    assert np.array_equal(synth.torch_to_host_bits(vals), v_o) and np.array_equal(mask_to_host(meta), m_o)
+    assert same_bits(synth.torch_to_host_bits(vals), v_o) and np.array_equal(mask_to_host(meta), m_o)
 
 
 def test_very_tall_matrix(orc, gpu):
@@ -218,7 +218,8 @@ def test_very_tall_matrix(orc, gpu):
 
 
 @pytest.mark.parametrize("out,n,dtype,alpha,beta", [(33, 4096, "bf16", 0.125, 0.125), (9, 1531, "bf16", 0.125, 0.125),
-                                                    (16, 1000, "f32", 0.3, 0.05), (5, 7, "f32", 1.0, 1.0)])
+                                                    (16, 1000, "f32", 0.3, 0.05), (5, 7, "f32", 1.0, 1.0),
+                                                    (11, 2048, "f16", 0.125, 0.25)])
 def test_ewma_trace_matches_oracle(orc, gpu, out, n, dtype, alpha, beta):
     """est / dev after every weight (the two curves of the paper's tracking figure) against the oracle's
     sequential fp32 walk and its fp64 walk: 1e-5 relative to the larger of the value and the row's mean

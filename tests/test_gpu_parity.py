@@ -81,7 +81,7 @@ def _layer_case(orc, gpu, out, n, tokens, dtype, seed, las=(0.5,), nms=((2, 4), 
     """Full parity of one layer shape; returns the number of tolerated scan-vs-oracle differences."""
     import torch
     from paper_2501_16376_amd import binding as b, synth
-    from gpu_util import to_device, check_ewma_mask, mask_to_host
+    from gpu_util import to_device, check_ewma_mask, mask_to_host, same_bits
     say(f"[case] out={out} in={n} tokens={tokens} dtype={dtype} seed={seed} pad={pitch_pad}")
     Wh, Xh = synth.layer_inputs(out, n, tokens, seed=seed, dtype=dtype, n_outlier=n_outlier)
     if pitch_pad:
@@ -134,23 +134,23 @@ def _layer_case(orc, gpu, out, n, tokens, dtype, seed, las=(0.5,), nms=((2, 4), 
     W1 = W_dev.clone() if not pitch_pad else to_device(Wp, gpu)[:, :n]
     b.swiftprune_apply(W1, to_device(mask_o.view(np.int32), gpu))
     torch.cuda.synchronize()
-    assert np.array_equal(synth.torch_to_host_bits(W1), ref)
+    assert same_bits(synth.torch_to_host_bits(W1), ref)
     W2 = W_dev.clone() if not pitch_pad else to_device(Wp, gpu)[:, :n]
     mk = torch.empty((out, (n + 31) // 32), dtype=torch.int32, device=gpu)
     b.swiftprune_score_select(W2, hr_dev, mk, la=las[0], flags=b.SP_APPLY_INPLACE | b.SP_SEQUENTIAL_ORDER)
     torch.cuda.synchronize()
-    assert np.array_equal(synth.torch_to_host_bits(W2), ref)
+    assert same_bits(synth.torch_to_host_bits(W2), ref)
     W3 = W_dev.clone() if not pitch_pad else to_device(Wp, gpu)[:, :n]
     b.swiftprune_score_select(W3, hr_dev, mk, la=las[0], flags=b.SP_APPLY_INPLACE)
     torch.cuda.synchronize()
     ref3 = orc.apply(Wh.copy(), mask_to_host(mk))
-    assert np.array_equal(synth.torch_to_host_bits(W3), ref3)      # fused apply agrees with its own mask
+    assert same_bits(synth.torch_to_host_bits(W3), ref3)      # fused apply agrees with its own mask
     if n % 4 == 0:
         nm_o, _ = orc.nm_select(Wh, hr_o, 2, 4)
         W4 = W_dev.clone() if not pitch_pad else to_device(Wp, gpu)[:, :n]
         b.swiftprune_nm_select(W4, hr_dev, 2, 4, mk, flags=b.SP_APPLY_INPLACE)
         torch.cuda.synchronize()
-        assert np.array_equal(synth.torch_to_host_bits(W4), orc.apply(Wh.copy(), nm_o))
+        assert same_bits(synth.torch_to_host_bits(W4), orc.apply(Wh.copy(), nm_o))
     if pitch_pad:                                                     # padding columns untouched
         for Wt in (W1, W2, W3):
             full = synth.torch_to_host_bits(Wt._base if Wt._base is not None else Wt)
@@ -175,6 +175,9 @@ def test_config1_fp32(orc, gpu):
     (5, 8, 3, "bf16", 0),              # one chunk
     (3, 1, 1, "f32", 0),               # a single column, a single token
     (1, 4096, 64, "bf16", 0),          # a single row
+    (300, 1376, 5000, "f16", 0),       # IEEE half storage: vector path
+    (33, 1001, 777, "f16", 0),         # IEEE half, element-wise path
+    (65, 1000, 300, "f16", 24),        # IEEE half, padded pitch
 ])
 def test_shapes(orc, gpu, out, n, tokens, dtype, pad):
     t = _layer_case(orc, gpu, out, n, tokens, dtype, seed=out + n, pitch_pad=pad,
@@ -183,19 +186,19 @@ def test_shapes(orc, gpu, out, n, tokens, dtype, pad):
 
 
 def test_random_small_shapes(orc, gpu):
-    """Forty seeded random shapes (1-40 rows, 1-1500 columns, 1-200 tokens, both dtypes, random row pitch):
+    """Forty-eight seeded random shapes (1-40 rows, 1-1500 columns, 1-200 tokens, three storage types, random row pitch):
     statistics to 1e-5, strict-order / N:M / apply bit-exact, scan path under the rounding rule."""
     import torch
     from paper_2501_16376_amd import binding as b, synth
-    from gpu_util import to_device, check_ewma_mask, mask_to_host
+    from gpu_util import to_device, check_ewma_mask, mask_to_host, same_bits
     rng = np.random.default_rng(2024)
-    for case in range(40):
+    for case in range(48):
         out = int(rng.integers(1, 41))
         n = int(rng.integers(1, 1501))
         if case % 3 == 0:
             n = max(8, n // 8 * 8)                                    # exercise the vector path too
         tokens = int(rng.integers(1, 201))
-        dtype = "bf16" if case % 2 == 0 else "f32"
+        dtype = ("bf16", "f32", "f16")[(case // 3 + case) % 3]
         pad = int(rng.choice([0, 0, 8, 3]))
         la = float(rng.choice([0.5, 0.2, -0.2, -0.9, 1.1]))
         say(f"[case {case}] out={out} in={n} tokens={tokens} {dtype} pad={pad} la={la}")
@@ -223,7 +226,7 @@ def test_random_small_shapes(orc, gpu):
         mk = torch.empty((out, (n + 31) // 32), dtype=torch.int32, device=gpu)
         b.swiftprune_score_select(W2, hr_dev, mk, la=la, flags=b.SP_APPLY_INPLACE)
         torch.cuda.synchronize()
-        assert np.array_equal(synth.torch_to_host_bits(W2), orc.apply(Wh.copy(), mask_to_host(mk)))
+        assert same_bits(synth.torch_to_host_bits(W2), orc.apply(Wh.copy(), mask_to_host(mk)))
         assert np.all(synth.torch_to_host_bits(W2._base)[:, n:] == 0)
 
 
@@ -297,7 +300,7 @@ def test_graph_capture_replays(orc, gpu):
     work and synchronisations between the replays."""
     import torch
     from paper_2501_16376_amd import binding as b, synth
-    from gpu_util import mask_to_host
+    from gpu_util import mask_to_host, same_bits
     out, n, tokens = 512, 2048, 4096
     X = synth.device_activations(tokens, n, seed=21, device=gpu)
     W0 = synth.device_weights(out, n, seed=22, device=gpu)
@@ -328,7 +331,7 @@ def test_graph_capture_replays(orc, gpu):
         torch.cuda.synchronize()
         assert np.array_equal(bufs.hr.cpu().numpy(), ref_hr), rep
         assert np.array_equal(mask_to_host(bufs.keep_mask), ref_mask), rep
-        assert np.array_equal(synth.torch_to_host_bits(Wg), ref_W), rep
+        assert same_bits(synth.torch_to_host_bits(Wg), ref_W), rep
 
 
 def test_degenerate_statistics(orc, gpu):
@@ -353,17 +356,17 @@ def test_all_ones_exact(orc, gpu):
     assert np.all(hr == np.float32(0.5) / (np.float32(1) - np.float32(1 / 1024)))
 
 
-def _full_size_layer(orc, gpu, out, n, seed, las=(0.5,)):
+def _full_size_layer(orc, gpu, out, n, seed, las=(0.5,), dtype="bf16"):
     """A Llama-sized layer at the full 128x2048 calibration tokens, in the launch configuration the
     benchmark times.  The oracle sees the same bits (copied to the host in token chunks) and computes
     everything itself; nothing it is given comes from the GPU path."""
     import torch
     from paper_2501_16376_amd import binding as b, synth
-    from gpu_util import to_device, check_ewma_mask
+    from gpu_util import to_device, check_ewma_mask, same_bits
     tokens = synth.CALIB_TOKENS
     say(f"[full] out={out} in={n} tokens={tokens}: generating")
-    X = synth.device_activations(tokens, n, seed=seed, device=gpu)
-    W = synth.device_weights(out, n, seed=seed + 1, device=gpu)
+    X = synth.device_activations(tokens, n, seed=seed, device=gpu, dtype=dtype)
+    W = synth.device_weights(out, n, seed=seed + 1, device=gpu, dtype=dtype)
     xsq_g, S_g, hr_g = _stats_gpu(X, n)
     say("[full] statistics on the oracle")
     acc = None
@@ -403,7 +406,7 @@ def _full_size_layer(orc, gpu, out, n, seed, las=(0.5,)):
     torch.cuda.synchronize()
     from gpu_util import mask_to_host
     assert np.array_equal(mask_to_host(bufs.keep_mask), m_scan)
-    assert np.array_equal(synth.torch_to_host_bits(W2), orc.apply(Wh.copy(), m_scan))
+    assert same_bits(synth.torch_to_host_bits(W2), orc.apply(Wh.copy(), m_scan))
 
 
 def test_full_size_q_proj(orc, gpu):
@@ -431,6 +434,10 @@ def test_full_size_gate_7b(orc, gpu):
 
 
 # Llama-2-70B-shaped layers (hidden 8192, intermediate 28672): the table's la for 50 % and 70 %
+def test_full_size_gate_8b_fp16(orc, gpu):
+    _full_size_layer(orc, gpu, 14336, 4096, seed=150, dtype="f16")
+
+
 def test_full_size_q_proj_70b(orc, gpu):
     _full_size_layer(orc, gpu, 8192, 8192, seed=700, las=(0.5, -0.2))
 
@@ -453,7 +460,7 @@ def test_matrix_beyond_4g_elements(orc, gpu):
     against the oracle one by one: EWMA (strict order and scan), 2:4, and the in-place apply."""
     import torch
     from paper_2501_16376_amd import binding as b, synth
-    from gpu_util import to_device, check_ewma_mask, mask_to_host
+    from gpu_util import to_device, check_ewma_mask, mask_to_host, same_bits
     out, n = 66000, 65536
     say(f"[case] {out} x {n} bf16: generating")
     g = torch.Generator(device=gpu)
@@ -489,7 +496,7 @@ def test_matrix_beyond_4g_elements(orc, gpu):
     W24 = W.clone()
     b.swiftprune_apply(W24, mask)
     torch.cuda.synchronize()
-    assert np.array_equal(synth.torch_to_host_bits(W24[rows]), orc.apply(Wh.copy(), nm_o))
+    assert same_bits(synth.torch_to_host_bits(W24[rows]), orc.apply(Wh.copy(), nm_o))
     del W24
 
     say("[case] scan selection fused with apply")
@@ -498,6 +505,6 @@ def test_matrix_beyond_4g_elements(orc, gpu):
     m_scan = mask_to_host(mask[rows])
     t = check_ewma_mask(orc, Wh, hr, A, B, 0.5, m_scan, cnt[rows].cpu().numpy())
     say(f"[case] scan vs oracle on {len(rows)} rows: {t} tolerated differences")
-    assert np.array_equal(synth.torch_to_host_bits(W[rows]), orc.apply(Wh.copy(), m_scan))
+    assert same_bits(synth.torch_to_host_bits(W[rows]), orc.apply(Wh.copy(), m_scan))
     total = int(cnt.to(torch.int64).sum().item())
     assert 0.45 < total / (out * n) < 0.60, total / (out * n)
