@@ -39,6 +39,8 @@ def parse():
     ap.add_argument("--la", type=float, default=0.5, help="threshold multiplier of the unstructured mode")
     ap.add_argument("--mode", default="unstructured", choices=["unstructured", "2:4", "4:8"])
     ap.add_argument("--tokens", type=int, default=128 * 2048)
+    ap.add_argument("--storage", default="bf16", choices=["bf16", "f16"],
+                    help="16-bit storage type of W and X (same bytes either way)")
     ap.add_argument("--shared-stats", action="store_true",
                     help="compute statistics once per distinct layer input (q/k/v and gate/up share)")
     ap.add_argument("--streams", type=int, default=1, choices=[1, 2],
@@ -86,12 +88,12 @@ def main():
     # ---- resident data: activations per distinct layer input, weights per (block, layer)
     t_setup = time.time()
     widths = {INPUT_OF[name]: n for name, _, n in block}
-    X = {key: synth.device_activations(T, n, seed=1000 + i, device=dev)
+    X = {key: synth.device_activations(T, n, seed=1000 + i, device=dev, dtype=args.storage)
          for i, (key, n) in enumerate(sorted(widths.items()))}
     weights, pristine = [], []
     for bi in range(args.blocks):
         for li, (name, out, n) in enumerate(block):
-            W = synth.device_weights(out, n, seed=10_000 + 16 * bi + li, device=dev)
+            W = synth.device_weights(out, n, seed=10_000 + 16 * bi + li, device=dev, dtype=args.storage)
             pristine.append(W)
             weights.append(W.clone())
     layers = [(name, out, n) for _ in range(args.blocks) for (name, out, n) in block]
@@ -214,7 +216,9 @@ def main():
     roofline = {"bound": "hbm",
                 "kernel": "stats_partial_kernel (events bracket swiftprune_layer_stats = it + the 4 us combine kernel)",
                 "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None,
-                "traffic": committed_traffic()}
+                # the committed counters were taken on the default workload (bf16 instantiation)
+                "traffic": committed_traffic() if (args.storage == "bf16" and args.model == "llama3-8b"
+                                                   and T == 128 * 2048) else None}
     if ev_pairs:
         tot_ms = sum(a.elapsed_time(b) for a, b, _ in ev_pairs)
         tot_bytes = sum(nb for _, _, nb in ev_pairs)
@@ -237,10 +241,10 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": f"{args.model}-shaped stack, {args.blocks} blocks x 7 linear layers, bf16 W, "
+        "config": {"workload": f"{args.model}-shaped stack, {args.blocks} blocks x 7 linear layers, {args.storage} W, "
                                f"{T} calibration tokens per layer, "
                                + (f"unstructured (la={la:g})" if nm is None else f"{args.mode} structured"),
-                   "storage": "bf16", "tokens": T, "blocks": args.blocks, "mode": args.mode,
+                   "storage": args.storage, "tokens": T, "blocks": args.blocks, "mode": args.mode,
                    "stats_calls_per_block": 4 if args.shared_stats else 7, "streams": args.streams,
                    "weights": n_weights},
         "seconds_per_model": round(ms_per_step * 1e-3, 5),
