@@ -19,7 +19,8 @@
  * inputs, a hand-worked row, threshold monotonicity, scale and permutation
  * invariances, reduction of N:M to per-group magnitude top-N under uniform
  * channel energy, per-group exact sort, the rank-one inverse identity behind
- * the score, statistics against a library sum.
+ * the score, statistics against a library sum, the binary16 decoder against a
+ * library's half type on all 65536 bit patterns.
  * Parity unpinned (the paper gives no value that fixes them): the reading
  * "x_q^2 is summed over all calibration tokens", the N:M ranking key and
  * tie-break, the degenerate-input conventions (S == 0, 1 - x_q^2/S <= 0).
