@@ -32,6 +32,35 @@ def test_exports_match_header(lib):
     assert set(binding.EXPORTS) == declared
 
 
+def test_header_is_plain_c_and_links(lib, tmp_path):
+    """The header compiles as C11 and as C++17 with warnings as errors, and a plain-C caller links against
+    the library and gets the documented host-side answers (no device call is made)."""
+    import subprocess
+    from paper_2501_16376_amd import binding
+    inc = os.path.join(ROOT, "include")
+    src = tmp_path / "caller.c"
+    src.write_text(
+        '#include "swiftprune.h"\n#include <stdio.h>\n'
+        "int main(void) {\n"
+        "    float la = 0.0f;\n"
+        "    sp_ewma_params p = {0.125f, 0.125f, 0.5f};\n"
+        "    if (swiftprune_la_for_sparsity(0.7f, &la) != SP_OK || la != -0.2f) return 1;\n"
+        "    if (swiftprune_layer_stats(NULL, 1, 1, 1, SP_F16, NULL, NULL, NULL, 0, 1, NULL, 0, NULL) != SP_EINVAL) return 2;\n"
+        "    if (swiftprune_nm_meta_words(4096, 2, 4) != 128) return 3;\n"
+        '    printf("%s %zu %g\\n", swiftprune_version(), swiftprune_stats_workspace_bytes(262144, 4096), (double)p.la);\n'
+        "    return 0;\n}\n")
+    subprocess.run(["gcc", "-std=c11", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", inc, "-c", str(src),
+                    "-o", str(tmp_path / "caller.o")], check=True)
+    subprocess.run(["g++", "-std=c++17", "-Wall", "-Wextra", "-Werror", "-I", inc, "-x", "c++", "-fsyntax-only",
+                    os.path.join(inc, "swiftprune.h")], check=True)
+    lib_dir = os.path.dirname(binding.LIB_PATH)
+    exe = tmp_path / "caller"
+    subprocess.run(["gcc", str(tmp_path / "caller.o"), "-o", str(exe), "-L", lib_dir, "-lswiftprune",
+                    f"-Wl,-rpath,{lib_dir}", "-Wl,-rpath,/opt/rocm/lib"], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    assert out[0] == "0.1.0" and int(out[1]) > 0 and float(out[2]) == 0.5
+
+
 def test_version_and_strerror(lib):
     from paper_2501_16376_amd import binding
     assert re.match(r"^\d+\.\d+\.\d+$", binding.swiftprune_version())
