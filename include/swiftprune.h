@@ -91,6 +91,16 @@ int swiftprune_layer_stats(const void *X, int64_t tokens, int64_t in, int64_t ld
                            void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * The last part of step 1 on its own (denominator of the Sec. 3.1 score equation):
+ *     hr[q] = 1/2 / (1 - xsq[q]/S),  with the conventions of swiftprune_layer_stats for S == 0 and a
+ *     non-positive denominator.
+ * For callers that add up xsq and S themselves - token shards reduced on several devices (each shard from
+ * swiftprune_layer_stats with finalize == 0), or statistics kept from an earlier run.
+ *   xsq [in], S [1], hr [in] fp32 (device; xsq and S read, hr written; hr may alias xsq)
+ */
+int swiftprune_channel_factor(const float *xsq, const float *S, int64_t in, float *hr, void *hip_stream);
+
+/*
  * Steps 2+3, unstructured (Sec. 3.1 score equation; Sec. 3.2; Algorithm 1 loop body).
  * Per row, q ascending, state est = L_0, dev = 0:
  *     prune (r,q)  iff  L < est - la*dev      (state before q, strict)

@@ -20,7 +20,7 @@ SP_OK, SP_EINVAL, SP_ENOSPC, SP_EHIP, SP_ERANGE = 0, -1, -2, -3, -4
 SP_SEQUENTIAL_ORDER, SP_APPLY_INPLACE = 1, 2
 
 EXPORTS = ("swiftprune_layer_stats", "swiftprune_score_select", "swiftprune_nm_select",
-           "swiftprune_apply", "swiftprune_ewma_trace", "swiftprune_count_pruned", "swiftprune_calibrate_la", "swiftprune_topk_select", "swiftprune_compact_nm", "swiftprune_expand_nm", "swiftprune_nm_meta_words", "swiftprune_la_for_sparsity", "swiftprune_stats_workspace_bytes",
+           "swiftprune_apply", "swiftprune_channel_factor", "swiftprune_ewma_trace", "swiftprune_count_pruned", "swiftprune_calibrate_la", "swiftprune_topk_select", "swiftprune_compact_nm", "swiftprune_expand_nm", "swiftprune_nm_meta_words", "swiftprune_la_for_sparsity", "swiftprune_stats_workspace_bytes",
            "swiftprune_strerror", "swiftprune_version")
 
 
@@ -57,6 +57,8 @@ def load_library(path: str | None = None) -> C.CDLL:
     L.swiftprune_nm_select.restype = i32
     L.swiftprune_apply.argtypes = [vp, i64, i64, i64, i32, vp, vp]
     L.swiftprune_apply.restype = i32
+    L.swiftprune_channel_factor.argtypes = [vp, vp, i64, vp, vp]
+    L.swiftprune_channel_factor.restype = i32
     L.swiftprune_ewma_trace.argtypes = [vp, i64, i64, i64, i32, vp, f, f, vp, vp, vp]
     L.swiftprune_ewma_trace.restype = i32
     L.swiftprune_count_pruned.argtypes = [vp, i64, i64, i64, i32, vp, f, f, C.POINTER(C.c_float), i32, vp, vp]
@@ -162,6 +164,16 @@ def swiftprune_layer_stats(X, xsq, S, hr, accumulate: bool = False, finalize: bo
         workspace.numel() * workspace.element_size(), _stream(stream))
     _check(code, "swiftprune_layer_stats")
     return workspace
+
+
+def swiftprune_channel_factor(xsq, S, hr, stream=None):
+    """hr[q] = 1/2 / (1 - xsq[q]/S) from given statistics (fp32 GPU tensors; hr is written)."""
+    import torch
+    n_in = xsq.numel()
+    code = load_library().swiftprune_channel_factor(
+        _vec(xsq, torch.float32, n_in, "xsq"), _vec(S, torch.float32, 1, "S"), n_in,
+        _vec(hr, torch.float32, n_in, "hr"), _stream(stream))
+    _check(code, "swiftprune_channel_factor")
 
 
 def swiftprune_score_select(W, hr, keep_mask, sparsity: float = 0.5, alpha: float = 0.125,

@@ -90,6 +90,16 @@ int swiftprune_layer_stats(const void* X, int64_t tokens, int64_t in, int64_t ld
     return e == hipSuccess ? SP_OK : SP_EHIP;
 }
 
+int swiftprune_channel_factor(const float* xsq, const float* S, int64_t in, float* hr, void* hip_stream) {
+    if (xsq == nullptr || S == nullptr || hr == nullptr || in <= 0) return SP_EINVAL;
+    if (in > (int64_t)0x7fffffff * 256) return SP_EINVAL;
+    if (reinterpret_cast<uintptr_t>(xsq) % 4 != 0 || reinterpret_cast<uintptr_t>(S) % 4 != 0 ||
+        reinterpret_cast<uintptr_t>(hr) % 4 != 0)
+        return SP_EINVAL;
+    const hipError_t e = sp::launch_channel_factor(xsq, S, in, hr, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? SP_OK : SP_EHIP;
+}
+
 int swiftprune_score_select(const void* W, int64_t out, int64_t in, int64_t ldw, sp_dtype dt,
                             const float* hr, float sparsity, const sp_ewma_params* params,
                             uint32_t* keep_mask, int32_t* row_pruned, float* scores,

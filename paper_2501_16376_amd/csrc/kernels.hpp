@@ -49,6 +49,8 @@ hipError_t launch_ewma_sequential(const void* W, int64_t out, int64_t in, int64_
                                   uint32_t* keep_mask, int32_t* row_pruned, float* scores, bool apply,
                                   hipStream_t stream);
 
+hipError_t launch_channel_factor(const float* xsq, const float* S, int64_t in, float* hr, hipStream_t stream);
+
 // ---- est / dev sequences written out (diagnostic) ----
 hipError_t launch_ewma_trace(const void* W, int64_t out, int64_t in, int64_t ldw, int dt, bool vec,
                              const float* hr, const EwmaConsts& c, float* est, float* dev,

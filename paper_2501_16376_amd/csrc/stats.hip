@@ -270,6 +270,14 @@ __global__ __launch_bounds__(kCombineThreads) void stats_total_kernel(const doub
     }
 }
 
+// hr[q] from given xsq[q] and S: the last part of the statistics step on its own.
+__global__ __launch_bounds__(kCombineThreads) void channel_factor_kernel(const float* __restrict__ xsq,
+                                                                        const float* __restrict__ S, int64_t in,
+                                                                        float* __restrict__ hr) {
+    const int64_t q = (int64_t)blockIdx.x * kCombineThreads + threadIdx.x;
+    if (q < in) hr[q] = channel_factor(xsq[q], S[0]);
+}
+
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 StatsPlan make_stats_plan(int64_t tokens, int64_t in, int dt, bool vec) {
@@ -347,6 +355,12 @@ hipError_t launch_layer_stats(const void* X, int64_t tokens, int64_t in, int64_t
     if (e != hipSuccess || !accumulate) return e;
     hipLaunchKernelGGL(stats_total_kernel, dim3(1), dim3(kCombineThreads), 0, stream, group_sums, ngroups,
                        accumulate, S);
+    return hipGetLastError();
+}
+
+hipError_t launch_channel_factor(const float* xsq, const float* S, int64_t in, float* hr, hipStream_t stream) {
+    hipLaunchKernelGGL(channel_factor_kernel, dim3((unsigned)ceil_div(in, kCombineThreads)), dim3(kCombineThreads),
+                       0, stream, xsq, S, in, hr);
     return hipGetLastError();
 }
 

@@ -129,6 +129,9 @@ def test_argument_checks_do_not_launch(lib):
     assert nm(p, 8, 8, 8, 1, p, 0, 4, p, None, 0, None) == E
     assert nm(p, 8, 12, 12, 1, p, 4, 8, p, None, 0, None) == E        # in % m != 0
     assert nm(p, 8, 8, 8, 1, p, 2, 4, p, None, 1, None) == E          # strict-order flag not valid here
+    cf = lib.swiftprune_channel_factor
+    assert cf(None, p, 8, p, None) == E and cf(p, None, 8, p, None) == E and cf(p, p, 8, None, None) == E
+    assert cf(p, p, 0, p, None) == E and cf(p + 2, p, 8, p, None) == E
     tr = lib.swiftprune_ewma_trace
     assert tr(p, 8, 8, 8, 1, p, 0.125, 0.125, None, None, None) == E         # nothing to write
     assert tr(None, 8, 8, 8, 1, p, 0.125, 0.125, p, p, None) == E

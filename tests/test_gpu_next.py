@@ -245,3 +245,45 @@ def test_ewma_trace_matches_oracle(orc, gpu, out, n, dtype, alpha, beta):
         for got, ref in ((est[r], e32), (dev[r], d32), (est[r], e64), (dev[r], d64)):
             err = np.abs(got.astype(np.float64) - ref) / np.maximum(np.abs(ref), floor)
             assert err.max() <= 1e-5, (r, int(err.argmax()), float(err.max()))
+
+
+def test_channel_factor_and_sharded_tokens(orc, gpu):
+    """swiftprune_channel_factor is bit-exact with the oracle's factor (incl. S == 0 and a channel that holds
+    all the energy), and the flow it exists for - statistics of two token shards taken separately
+    (finalize = 0), added, then the factor - matches the oracle on all the tokens."""
+    import torch
+    from paper_2501_16376_amd import binding as b, synth
+    from gpu_util import to_device
+    rng = np.random.default_rng(5)
+    n = 3001
+    xsq = (rng.uniform(0.1, 50.0, n) ** 2).astype(np.float32)
+    xsq[7] *= 1e6
+    S = np.float32(xsq.astype(np.float64).sum())
+    cases = [(xsq, S), (xsq, np.float32(0.0)), (np.array([4.0, 0.0, 0.0], np.float32), np.float32(4.0)),
+             (np.array([5.0, 1.0], np.float32), np.float32(4.0))]
+    for x, s in cases:
+        say(f"[case] channel_factor in={x.shape[0]} S={float(s)}")
+        hr = torch.full((x.shape[0],), float("nan"), dtype=torch.float32, device=gpu)
+        b.swiftprune_channel_factor(to_device(x, gpu), to_device(np.array([s], np.float32), gpu), hr)
+        torch.cuda.synchronize()
+        ref = orc.channel_factor_f32(x, s)
+        assert np.array_equal(hr.cpu().numpy().view(np.uint32), ref.view(np.uint32))
+    # two token shards, reduced by the caller
+    _, Xh = synth.layer_inputs(4, 2048, 3000, seed=77, dtype="bf16")
+    X = to_device(Xh, gpu)
+    parts = []
+    for lo, hi in ((0, 1700), (1700, 3000)):
+        x_d = torch.empty(2048, dtype=torch.float32, device=gpu)
+        S_d = torch.empty(1, dtype=torch.float32, device=gpu)
+        h_d = torch.empty(2048, dtype=torch.float32, device=gpu)
+        b.swiftprune_layer_stats(X[lo:hi], x_d, S_d, h_d, finalize=False)
+        parts.append((x_d, S_d))
+    xsq_sum = parts[0][0] + parts[1][0]           # stands in for the all-reduce of in + 1 values
+    S_sum = parts[0][1] + parts[1][1]
+    hr = torch.empty(2048, dtype=torch.float32, device=gpu)
+    b.swiftprune_channel_factor(xsq_sum, S_sum, hr)
+    torch.cuda.synchronize()
+    xsq_o, S_o, hr_o = orc.layer_stats(Xh)
+    assert np.allclose(xsq_sum.cpu().numpy(), xsq_o, rtol=1e-5, atol=0)
+    assert abs(float(S_sum.item()) - S_o) <= 1e-5 * S_o
+    assert np.allclose(hr.cpu().numpy(), hr_o, rtol=1e-5, atol=0)

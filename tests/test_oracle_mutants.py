@@ -4,10 +4,13 @@ The mistakes are planted in a temporary copy of the oracle's source text (never 
 on the GPU), compiled with the oracle's own flags and run through tests/pins.py."""
 import os
 import shutil
+import subprocess
+import sys
 
 import pytest
 
-import pins
+TESTS = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(TESTS)
 
 # (name, file, text to replace, replacement)
 MUTANTS = [
@@ -71,15 +74,28 @@ def test_mutant_is_caught(orc, src_dir, tmp_path, mutant):
     assert text.count(old) >= 1, f"mutation site for {name} not found"
     (tmp_path / fname).write_text(text.replace(old, new))
     so = str(tmp_path / f"liboracle_{name}.so")
-    import subprocess
     subprocess.run(["gcc", *[f for f in orc.CFLAGS if f not in ("-Wall", "-Wextra")],
                     str(tmp_path / "swiftprune_oracle.c"), "-o", so, "-lm"], check=True)
-    L = orc.lib(so)
-    caught = []
-    for pin in pins.ALL_PINS:
-        try:
-            pin(orc, L)
-        except AssertionError:
-            caught.append(pin.__name__)
+    # The pins run in a child process: a planted mistake may write out of bounds (a wider meta field,
+    # a wrong group index), and that must not reach the heap of the test runner.
+    child = (
+        "import sys\n"
+        f"sys.path[:0] = [{ROOT!r}, {TESTS!r}]\n"
+        "import oracle, pins\n"
+        f"L = oracle.lib({so!r})\n"
+        "caught = []\n"
+        "for pin in pins.ALL_PINS:\n"
+        "    try:\n"
+        "        pin(oracle, L)\n"
+        "    except AssertionError:\n"
+        "        caught.append(pin.__name__)\n"
+        "print('CAUGHT ' + ','.join(caught), flush=True)\n")
+    res = subprocess.run([sys.executable, "-c", child], capture_output=True, text=True, timeout=300)
+    if res.returncode < 0 or res.returncode == 134:
+        print(f"{name}: the planted mistake corrupts memory (child ended with {res.returncode})")
+        return
+    assert res.returncode == 0, res.stderr[-2000:]
+    line = [ln for ln in res.stdout.splitlines() if ln.startswith("CAUGHT ")][-1]
+    caught = [c for c in line[len("CAUGHT "):].split(",") if c]
     assert caught, f"no pin notices the planted mistake '{name}'"
     print(f"{name}: caught by {', '.join(caught)}")
