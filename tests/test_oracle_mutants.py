@@ -51,7 +51,7 @@ MUTANTS = [
     ("topk_tie_break_reversed", "swiftprune_oracle.c", "return (x->index > y->index) - (x->index < y->index);",
      "return (x->index < y->index) - (x->index > y->index);"),
     ("topk_off_by_one", "swiftprune_oracle.c", "for (int64_t j = k; j < in; ++j) {", "for (int64_t j = k + 1; j < in; ++j) {"),
-    ("compact_wrong_field_width", "swiftprune_oracle.c", "return m_group == 4 ? 2 : 4;", "return m_group == 4 ? 4 : 4;"),
+    ("compact_wrong_field_width", "swiftprune_oracle.c", "return m_group == 4 ? 2 : 4;", "return m_group == 4 ? 2 : 2;"),
     ("compact_takes_pruned", "swiftprune_oracle.c",
      "if (!((keep_mask[r * words + (q >> 5)] >> (q & 31)) & 1u)) continue;\n                int64_t f",
      "if (((keep_mask[r * words + (q >> 5)] >> (q & 31)) & 1u)) continue;\n                int64_t f"),
