@@ -33,9 +33,10 @@ def parse():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--blocks", type=int, default=32, help="decoder blocks in the stack (32 = the 8B shape)")
-    ap.add_argument("--model", default="llama3-8b", choices=["llama3-8b", "llama2-7b", "llama2-70b"],
+    ap.add_argument("--model", default="llama3-8b",
+                    choices=["llama3-8b", "llama2-7b", "llama2-13b", "llama2-70b", "pythia-2.8b"],
                     help="block shape; llama2-70b has 80 blocks of 1.7 GB: pass --blocks <= 32 so that the "
-                         "weights, their pristine copy and the activations fit in HBM")
+                         "weights, their pristine copy and the activations fit in HBM (llama2-13b has 40 blocks)")
     ap.add_argument("--la", type=float, default=0.5, help="threshold multiplier of the unstructured mode")
     ap.add_argument("--mode", default="unstructured", choices=["unstructured", "2:4", "4:8"])
     ap.add_argument("--tokens", type=int, default=128 * 2048)
@@ -61,7 +62,8 @@ def parse():
 
 # which activation feeds which layer of a block
 INPUT_OF = {"q": "attn_in", "k": "attn_in", "v": "attn_in", "o": "attn_out",
-            "gate": "mlp_in", "up": "mlp_in", "down": "mlp_mid"}
+            "gate": "mlp_in", "up": "mlp_in", "down": "mlp_mid",
+            "qkv": "attn_in", "dense": "attn_out", "h_to_4h": "mlp_in", "4h_to_h": "mlp_mid"}
 
 
 def main():
@@ -79,8 +81,7 @@ def main():
     torch.cuda.set_device(dev)
     sp.load_library()
 
-    block = {"llama3-8b": synth.LLAMA3_8B_BLOCK, "llama2-7b": synth.LLAMA2_7B_BLOCK,
-             "llama2-70b": synth.LLAMA2_70B_BLOCK}[args.model]
+    block = synth.MODEL_BLOCKS[args.model][0]
     T = args.tokens
     nm = None if args.mode == "unstructured" else tuple(int(x) for x in args.mode.split(":"))
     la = args.la
@@ -184,6 +185,13 @@ def main():
         for W, P in zip(weights, pristine):
             W.copy_(P)
 
+    # The host must not pause while it feeds the GPU: a full collection of Python's garbage collector
+    # (tens of ms with torch loaded) that falls right after a synchronisation shows up as GPU idle time
+    # inside one step.  Collect now, then keep the collector off until the timed steps are done.
+    import gc
+    gc.collect()
+    gc.disable()
+
     for _ in range(args.warmup):          # identical to a timed step, instrumentation included
         restore()
         torch.cuda.synchronize()
@@ -204,6 +212,7 @@ def main():
         step_events.append((s0, s1))
     torch.cuda.synchronize()
     wall_s = time.time() - t_wall0
+    gc.enable()
     step_ms = [a.elapsed_time(b) for a, b in step_events]
     ms_per_step = sum(step_ms) / len(step_ms)
 
@@ -241,11 +250,11 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": f"{args.model}-shaped stack, {args.blocks} blocks x 7 linear layers, {args.storage} W, "
+        "config": {"workload": f"{args.model}-shaped stack, {args.blocks} blocks x {len(block)} linear layers, {args.storage} W, "
                                f"{T} calibration tokens per layer, "
                                + (f"unstructured (la={la:g})" if nm is None else f"{args.mode} structured"),
                    "storage": args.storage, "tokens": T, "blocks": args.blocks, "mode": args.mode,
-                   "stats_calls_per_block": 4 if args.shared_stats else 7, "streams": args.streams,
+                   "stats_calls_per_block": len(widths) if args.shared_stats else len(block), "streams": args.streams,
                    "weights": n_weights},
         "seconds_per_model": round(ms_per_step * 1e-3, 5),
         "step_ms_min_max": [round(min(step_ms), 3), round(max(step_ms), 3)],

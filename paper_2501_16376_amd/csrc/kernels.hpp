@@ -16,7 +16,7 @@ struct StatsPlan {
     int strip_units;         // units per column strip (<= 256, one per lane of a workgroup)
     int nstrips;             // column strips
     int splits;              // workgroups per strip; row batches are dealt to them round-robin
-    int unroll;              // rows per batch (4 or 8)
+    int unroll;              // rows per batch (4, 8 or 16)
     int64_t rows_per_split;  // upper bound of the tokens one workgroup sees
     int combine_groups;      // workgroups of the combine kernel (64 columns each)
     size_t partial_floats;   // splits * units * epu

@@ -290,13 +290,30 @@ StatsPlan make_stats_plan(int64_t tokens, int64_t in, int dt, bool vec) {
     if (su > kStatsThreads) su = kStatsThreads;
     p.strip_units = (int)su;
     p.nstrips = (int)ceil_div(p.units, su);
-    // Rows in flight per lane and workgroups per compute unit, from sweeps over the Llama widths
-    // (4096, 8192, 11008, 14336, 28672) on MI355X: a power-of-two number of strips maps every strip
-    // to a fixed subset of the 8 XCDs and does best with 4 rows in flight and 1.5 workgroups per
-    // compute unit; otherwise 8 rows and 1 workgroup.
+    // Rows in flight per lane and workgroups, from sweeps over 2560 ... 28672 bf16 columns at 262144 tokens
+    // on MI355X (rows in flight 4 / 8 / 16 against 256 / 384 / 512 / 768 workgroups):
+    //  * strips much narrower than the workgroup (fewer than 70 % of the lanes used, e.g. 2560 columns =
+    //    2 x 160 lanes): every lane keeps 16 rows in flight, or too few bytes are in flight
+    //  * strips whose last wavefront is less than half used (5120 columns = 3 x 216 lanes): 4 rows and two
+    //    workgroups per compute unit (11008 = 6 x 232 lanes is better off with the rule for full strips)
+    //  * full strips: a power-of-two number of strips maps every strip to a fixed subset of the 8 XCDs and
+    //    does best with 4 rows and 1.5 workgroups per compute unit; otherwise 8 rows and 1 workgroup.
     const bool pow2_strips = (p.nstrips & (p.nstrips - 1)) == 0;
-    p.unroll = pow2_strips ? 4 : 8;
-    const int64_t target = pow2_strips ? kStatsComputeUnits * 3 / 2 : kStatsComputeUnits;
+    const int fill_pct = (int)(su * 100 / kStatsThreads);
+    int64_t target;
+    if (fill_pct < 70) {
+        p.unroll = 16;
+        target = kStatsComputeUnits;
+    } else if (fill_pct < 88) {
+        p.unroll = 4;
+        target = kStatsComputeUnits * 2;
+    } else if (pow2_strips) {
+        p.unroll = 4;
+        target = kStatsComputeUnits * 3 / 2;
+    } else {
+        p.unroll = 8;
+        target = kStatsComputeUnits;
+    }
     int64_t splits = target / p.nstrips;
     const int64_t batches = ceil_div(tokens, p.unroll);
     if (splits > batches) splits = batches;
@@ -320,7 +337,10 @@ template <int DT, int EPU>
 static hipError_t launch_partial(const void* X, int64_t tokens, int64_t ldx, const StatsPlan& p,
                                  float* partials, double* group_sums, hipStream_t stream) {
     dim3 grid((unsigned)p.nstrips, (unsigned)p.splits);
-    if (p.unroll == 4)
+    if (p.unroll == 16)
+        hipLaunchKernelGGL((stats_partial_kernel<DT, EPU, 16>), grid, dim3(kStatsThreads), 0, stream, X, tokens,
+                           p.units, p.strip_units, ldx, partials, group_sums);
+    else if (p.unroll == 4)
         hipLaunchKernelGGL((stats_partial_kernel<DT, EPU, 4>), grid, dim3(kStatsThreads), 0, stream, X, tokens,
                            p.units, p.strip_units, ldx, partials, group_sums);
     else

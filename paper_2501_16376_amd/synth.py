@@ -28,6 +28,15 @@ LLAMA3_8B_BLOCK = [("q", 4096, 4096), ("k", 1024, 4096), ("v", 1024, 4096), ("o"
                    ("gate", 14336, 4096), ("up", 14336, 4096), ("down", 4096, 14336)]
 LLAMA2_70B_BLOCK = [("q", 8192, 8192), ("k", 1024, 8192), ("v", 1024, 8192), ("o", 8192, 8192),
                     ("gate", 28672, 8192), ("up", 28672, 8192), ("down", 8192, 28672)]
+# the other two models of the paper's main table (Sec. 4.1): LLaMA-2-13B (40 blocks) and Pythia-2.8B
+# (32 blocks, GPT-NeoX layout: fused query/key/value, attention output, two MLP matrices)
+LLAMA2_13B_BLOCK = [("q", 5120, 5120), ("k", 5120, 5120), ("v", 5120, 5120), ("o", 5120, 5120),
+                    ("gate", 13824, 5120), ("up", 13824, 5120), ("down", 5120, 13824)]
+PYTHIA_2_8B_BLOCK = [("qkv", 7680, 2560), ("dense", 2560, 2560), ("h_to_4h", 10240, 2560),
+                     ("4h_to_h", 2560, 10240)]
+MODEL_BLOCKS = {"llama3-8b": (LLAMA3_8B_BLOCK, 32), "llama2-7b": (LLAMA2_7B_BLOCK, 32),
+                "llama2-13b": (LLAMA2_13B_BLOCK, 40), "llama2-70b": (LLAMA2_70B_BLOCK, 80),
+                "pythia-2.8b": (PYTHIA_2_8B_BLOCK, 32)}
 CALIB_TOKENS = 128 * 2048
 
 
