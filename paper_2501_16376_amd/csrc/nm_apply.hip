@@ -63,20 +63,22 @@ __device__ __forceinline__ uint32_t nm_keep_bits16(const float* L, int n_prune, 
     return keep;
 }
 
-// A tile is kRows rows x 256 chunks (2048 columns).  grid = col_tiles * row_groups (one dimension, column
-// tile fastest, so consecutive workgroups touch consecutive memory), block = 256.
+// A wavefront owns a tile of kRows rows x 64 chunks (512 columns); tiles are numbered column-first, so the
+// four wavefronts of a workgroup and consecutive workgroups touch consecutive memory, and a row width that
+// is not a multiple of 2048 columns wastes at most part of one wavefront.  grid = ceil(tiles / 4), block = 256.
 template <int DT, bool VEC, int M>
 __global__ __launch_bounds__(kColThreads) void nm_select_kernel(
     void* __restrict__ W, int64_t out, int64_t in, int64_t ldw, const float* __restrict__ hr,
     int n_prune, uint32_t* __restrict__ keep_mask, float* __restrict__ scores, int apply,
     unsigned col_tiles) {
     const int lane = threadIdx.x & (kWave - 1);
-    const int64_t chunk = (int64_t)(blockIdx.x % col_tiles) * kColThreads + threadIdx.x;
+    const int64_t tile = (int64_t)blockIdx.x * (kColThreads / kWave) + (threadIdx.x >> 6);
+    const int64_t chunk = (tile % col_tiles) * kWave + lane;
     const int64_t q0 = chunk * 8;
     const int valid = (int)min((int64_t)8, max((int64_t)0, in - q0));
-    const int64_t row0 = (int64_t)(blockIdx.x / col_tiles) * kRows;
+    const int64_t row0 = (tile / col_tiles) * kRows;
     const int64_t mask_words = (in + 31) >> 5;
-    const int nrows = (int)min((int64_t)kRows, out - row0);
+    const int nrows = (int)max((int64_t)0, min((int64_t)kRows, out - row0));  // 0 for a wavefront past the last tile
 
     Factor8 f;
     if (VEC) { if (valid) f.load_vec(hr, q0); else f.load_elems(hr, q0, 0); }
@@ -93,7 +95,7 @@ __global__ __launch_bounds__(kColThreads) void nm_select_kernel(
     }
 #pragma unroll
     for (int r = 0; r < kRows; ++r) {
-        if (r >= nrows) break;  // uniform over the workgroup
+        if (r >= nrows) break;  // uniform over the wavefront
         float L[8];
 #pragma unroll
         for (int k = 0; k < 8; ++k) L[k] = score_of(w[r].get(k), f.v[k]);
@@ -118,13 +120,14 @@ __global__ __launch_bounds__(kColThreads) void apply_kernel(void* __restrict__ W
                                                            int64_t ldw,
                                                            const uint32_t* __restrict__ keep_mask,
                                                            unsigned col_tiles) {
-    const int64_t chunk = (int64_t)(blockIdx.x % col_tiles) * kColThreads + threadIdx.x;
+    const int64_t tile = (int64_t)blockIdx.x * (kColThreads / kWave) + (threadIdx.x >> 6);
+    const int64_t chunk = (tile % col_tiles) * kWave + (threadIdx.x & (kWave - 1));
     const int64_t q0 = chunk * 8;
     const int valid = (int)min((int64_t)8, max((int64_t)0, in - q0));
     if (valid == 0) return;
-    const int64_t row0 = (int64_t)(blockIdx.x / col_tiles) * kRows;
+    const int64_t row0 = (tile / col_tiles) * kRows;
     const int64_t mask_words = (in + 31) >> 5;
-    const int nrows = (int)min((int64_t)kRows, out - row0);
+    const int nrows = (int)max((int64_t)0, min((int64_t)kRows, out - row0));  // 0 for a wavefront past the last tile
     const int shift = (int)(q0 & 31);
 
     Chunk8<DT> w[kRows];
@@ -152,10 +155,11 @@ static hipError_t launch_nm_t(const void* W, int64_t out, int64_t in, int64_t ld
                               int n_keep, int m_group, uint32_t* keep_mask, float* scores, bool apply,
                               hipStream_t stream) {
     const int64_t chunks = (in + 7) / 8;
-    const unsigned col_tiles = (unsigned)((chunks + kColThreads - 1) / kColThreads);
+    const unsigned col_tiles = (unsigned)((chunks + kWave - 1) / kWave);
     const int64_t tiles = (int64_t)col_tiles * ((out + kRows - 1) / kRows);
-    if (tiles > 0x7fffffff) return hipErrorInvalidValue;
-    dim3 grid((unsigned)tiles);
+    const int64_t groups = (tiles + kColThreads / kWave - 1) / (kColThreads / kWave);
+    if (groups > 0x7fffffff) return hipErrorInvalidValue;
+    dim3 grid((unsigned)groups);
     void* Wm = const_cast<void*>(W);
     const int n_prune = m_group - n_keep;
     const int ap = apply ? 1 : 0;
@@ -191,10 +195,11 @@ hipError_t launch_nm_select(const void* W, int64_t out, int64_t in, int64_t ldw,
 hipError_t launch_apply(void* W, int64_t out, int64_t in, int64_t ldw, int dt, bool vec,
                         const uint32_t* keep_mask, hipStream_t stream) {
     const int64_t chunks = (in + 7) / 8;
-    const unsigned col_tiles = (unsigned)((chunks + kColThreads - 1) / kColThreads);
+    const unsigned col_tiles = (unsigned)((chunks + kWave - 1) / kWave);
     const int64_t tiles = (int64_t)col_tiles * ((out + kRows - 1) / kRows);
-    if (tiles > 0x7fffffff) return hipErrorInvalidValue;
-    dim3 grid((unsigned)tiles);
+    const int64_t groups = (tiles + kColThreads / kWave - 1) / (kColThreads / kWave);
+    if (groups > 0x7fffffff) return hipErrorInvalidValue;
+    dim3 grid((unsigned)groups);
     return with_dtype(dt, [&](auto tag) {
         constexpr int DT = decltype(tag)::value;
         if (vec) hipLaunchKernelGGL((apply_kernel<DT, true>), grid, dim3(kColThreads), 0, stream, W, out, in, ldw, keep_mask, col_tiles);
