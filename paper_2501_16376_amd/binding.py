@@ -9,7 +9,6 @@ at first use.
 from __future__ import annotations
 
 import ctypes as C
-import math
 import os
 
 HERE = os.path.dirname(os.path.abspath(__file__))
