@@ -434,6 +434,16 @@ def test_full_size_gate_7b(orc, gpu):
 
 
 # Llama-2-70B-shaped layers (hidden 8192, intermediate 28672): the table's la for 50 % and 70 %
+def test_full_size_q_proj_13b(orc, gpu):
+    """5120 columns: three strips whose last wavefront is a third full (4 rows in flight, 512 workgroups)."""
+    _full_size_layer(orc, gpu, 5120, 5120, seed=160)
+
+
+def test_full_size_qkv_pythia(orc, gpu):
+    """2560 columns: two strips of 160 lanes (16 rows in flight per lane)."""
+    _full_size_layer(orc, gpu, 7680, 2560, seed=170)
+
+
 def test_full_size_gate_8b_fp16(orc, gpu):
     _full_size_layer(orc, gpu, 14336, 4096, seed=150, dtype="f16")
 
