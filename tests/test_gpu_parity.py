@@ -518,3 +518,40 @@ def test_matrix_beyond_4g_elements(orc, gpu):
     assert same_bits(synth.torch_to_host_bits(W[rows]), orc.apply(Wh.copy(), m_scan))
     total = int(cnt.to(torch.int64).sum().item())
     assert 0.45 < total / (out * n) < 0.60, total / (out * n)
+
+
+def test_fp16_all_finite_bit_patterns(orc, gpu):
+    """IEEE half storage with random finite bit patterns (subnormals, +-65504, both zeros) in X and W: the
+    conversions in the streaming kernel (mixed-precision multiply-add), in the vector path and in the
+    element-wise path are exact, so statistics stay within 1e-5 and scores / strict-order masks bit-exact."""
+    import torch
+    from paper_2501_16376_amd import binding as b
+    from gpu_util import to_device, check_ewma_mask
+    rng = np.random.default_rng(1616)
+    for out, n, tokens in ((40, 2048, 300), (9, 1003, 77)):
+        say(f"[case] fp16 bit patterns out={out} in={n} tokens={tokens}")
+        def patterns(shape):
+            bits = rng.integers(0, 1 << 16, size=shape, dtype=np.uint16)
+            bits[(bits & 0x7c00) == 0x7c00] &= 0x83ff          # infinities and NaNs become subnormals
+            return bits.view(np.float16)
+        Xh, Wh = patterns((tokens, n)), patterns((out, n))
+        Xh[:, 0] = np.float16(0.0)                              # a dead channel
+        X_dev, W_dev = to_device(Xh, gpu), to_device(Wh, gpu)
+        xsq_o, S_o, hr_o = orc.layer_stats(Xh)
+        xsq_g, S_g, hr_g = _stats_gpu(X_dev, n)
+        assert xsq_g[0] == 0.0 and xsq_o[0] == 0.0
+        assert np.allclose(xsq_g, xsq_o, rtol=1e-5, atol=0) and abs(S_g - S_o) <= 1e-5 * S_o
+        assert np.allclose(hr_g, hr_o, rtol=1e-5, atol=0)
+        hr_dev = to_device(hr_o, gpu)
+        mask_o, cnt_o, sc_o = orc.ewma_select(Wh, hr_o, A, B, 0.5, want_scores=True)
+        m_seq, c_seq, sc_seq = _select_gpu(W_dev, hr_dev, 0.5, flags=b.SP_SEQUENTIAL_ORDER, want_scores=True)
+        assert np.array_equal(sc_seq.view(np.uint32), sc_o.view(np.uint32))
+        assert np.array_equal(m_seq, mask_o) and np.array_equal(c_seq, cnt_o)
+        m_scan, c_scan, sc_scan = _select_gpu(W_dev, hr_dev, 0.5, want_scores=True)
+        assert np.array_equal(sc_scan.view(np.uint32), sc_o.view(np.uint32))
+        check_ewma_mask(orc, Wh, hr_o, A, B, 0.5, m_scan, c_scan)
+        m_fast, c_fast, _ = _select_gpu(W_dev, hr_dev, 0.5)
+        check_ewma_mask(orc, Wh, hr_o, A, B, 0.5, m_fast, c_fast)
+        if n % 4 == 0:
+            nm_g, _ = _nm_gpu(W_dev, hr_dev, 2, 4)
+            assert np.array_equal(nm_g, orc.nm_select(Wh, hr_o, 2, 4)[0])
