@@ -48,8 +48,8 @@ typedef enum {
 } sp_status;
 
 /* EWMA parameters of Algorithm 1.  alpha, beta in (0, 1];  la is the
- * threshold multiplier (the table "parameter adjustment under different
- * pruning ratios" maps ratios to la).  The paper's only numeric alpha/beta is
+ * threshold multiplier (the table of Sec. 3.1 maps pruning ratios of 50-90 %
+ * to la).  The paper's only numeric alpha/beta is
  * 0.125 (Sec. 4.2).  If la is NaN it is looked up from `sparsity`. */
 typedef struct {
     float alpha;
@@ -64,7 +64,7 @@ typedef struct {
 #define SP_APPLY_INPLACE 2u    /* also zero the pruned weights of W in place (step 4 fused in) */
 
 /*
- * Step 1 (Algorithm 1, first statement; Sec. 3.1 "S is the sum of all x_i^2").
+ * Step 1 (Algorithm 1, first statement; Sec. 3.1 defines S as the sum of the squared activations).
  *
  *   X          [tokens, in], pitch ldx, dtype dt               (device, read)
  *   xsq        [in] fp32: accumulate == 0 -> overwritten with sum_t X[t,q]^2;
