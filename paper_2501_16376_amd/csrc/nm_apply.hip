@@ -17,23 +17,28 @@ namespace sp {
 constexpr int kRows = 8;        // rows per lane
 constexpr int kColThreads = 256;
 
-// keep bits of the 8 scores of a lane for group size M <= 8
+// keep bits of the 8 scores of a lane for group size M <= 8.  One comparison per pair serves both of its
+// entries: with c(p,i) = [L_p <= L_i] for p < i,
+//     rank_i = #{p < i : L_p <= L_i} + #{p > i : L_p < L_i} = sum_{p<i} c(p,i) + (M-1-i) - sum_{p>i} c(i,p).
 template <int M>
 __device__ __forceinline__ uint32_t nm_keep_bits(const float* L, int n_prune) {
     uint32_t keep = 0u;
 #pragma unroll
     for (int g = 0; g < 8; g += M) {
+        int rank[M];
 #pragma unroll
-        for (int i = 0; i < M; ++i) {
-            int rank = 0;
+        for (int i = 0; i < M; ++i) rank[i] = M - 1 - i;
 #pragma unroll
-            for (int p = 0; p < M; ++p) {
-                if (p == i) continue;
-                const bool less = (p < i) ? (L[g + p] <= L[g + i]) : (L[g + p] < L[g + i]);
-                rank += less ? 1 : 0;
+        for (int i = 1; i < M; ++i) {
+#pragma unroll
+            for (int p = 0; p < i; ++p) {
+                const int c = (L[g + p] <= L[g + i]) ? 1 : 0;
+                rank[i] += c;
+                rank[p] -= c;
             }
-            keep |= (rank >= n_prune) ? (1u << (g + i)) : 0u;
         }
+#pragma unroll
+        for (int i = 0; i < M; ++i) keep |= (rank[i] >= n_prune) ? (1u << (g + i)) : 0u;
     }
     return keep;
 }
