@@ -74,7 +74,7 @@ def _declare(L: C.CDLL) -> C.CDLL:
     L.oracle_nm_select_f32.argtypes = [_vp, _i64, _i64, _i64, _i32, _vp, _i32, _i32, _vp, _vp]
     L.oracle_nm_select_f64.argtypes = [_vp, _i64, _i64, _i64, _i32, _vp, _i32, _i32, _vp, _vp]
     L.oracle_ewma_select_literal_f32.argtypes = [_vp, _i64, _i64, _i64, _i32, _vp, _f, _f, _f, _f,
-                                                 _vp, _vp, _vp]
+                                                 _vp, _vp, _vp, _vp, _vp]
     L.oracle_topk_select_f32.argtypes = [_vp, _i64, _i64, _i64, _i32, _vp, _vp, _i64, _vp]
     L.oracle_compact_nm.argtypes = [_vp, _i64, _i64, _i64, _i32, _vp, _i32, _i32, _vp, _vp]
     L.oracle_expand_nm.argtypes = [_vp, _vp, _i64, _i64, _i32, _i32, _i32, _vp]
@@ -201,17 +201,22 @@ def ewma_select(W: np.ndarray, hr: np.ndarray, alpha, beta, la, precision: str =
     return mask, cnt, sc
 
 
-def ewma_select_literal(W: np.ndarray, xsq: np.ndarray, S, alpha, beta, la, L=None):
-    """Algorithm 1 as printed (S updated when pruning): (keep_mask, row_pruned, n_effective_S_updates)."""
+def ewma_select_literal(W: np.ndarray, xsq: np.ndarray, S, alpha, beta, la, details: bool = False, L=None):
+    """Algorithm 1 as printed (S updated when pruning): (keep_mask, row_pruned, n_effective_S_updates);
+    with details also (scores float32[out, in], S of every row after its last element)."""
     ptr, out, n, ld, dt = _mat(W)
     xsq = np.ascontiguousarray(xsq, dtype=np.float32)
     mask = np.empty((out, (n + 31) // 32), dtype=np.uint32)
     cnt = np.empty(out, dtype=np.int32)
     eff = np.zeros(1, dtype=np.int64)
+    sc = np.empty((out, n), dtype=np.float32) if details else None
+    S_rows = np.empty(out, dtype=np.float32) if details else None
     (L or lib()).oracle_ewma_select_literal_f32(ptr, out, n, ld, dt, xsq.ctypes.data,
                                                 float(np.float32(S)), float(alpha), float(beta),
                                                 float(la), mask.ctypes.data, cnt.ctypes.data,
-                                                eff.ctypes.data)
+                                                eff.ctypes.data, _p(sc), _p(S_rows))
+    if details:
+        return mask, cnt, int(eff[0]), sc, S_rows
     return mask, cnt, int(eff[0])
 
 

@@ -193,13 +193,15 @@ void oracle_score_f64(const void *W, int64_t out, int64_t in, int64_t ldw, int d
  * state-update table), and the score is evaluated per element with the
  * current S:  L_i = (0.5*w*w) / (1 - xsq[i]/S_r).
  * Used as a cross-check of the fixed-S form above.  n_effective (nullable)
- * receives how many of the subtractions changed the bits of S_r, summed over rows.
+ * receives how many of the subtractions changed the bits of S_r, summed over rows;
+ * scores (nullable, [out, in]) the score of every element as it was evaluated,
+ * S_rows (nullable, [out]) the value of S_r after the last element of each row.
  */
 void oracle_ewma_select_literal_f32(const void *W, int64_t out, int64_t in, int64_t ldw,
                                     int dt, const float *xsq, float S,
                                     float alpha, float beta, float la,
                                     uint32_t *keep_mask, int32_t *row_pruned,
-                                    int64_t *n_effective)
+                                    int64_t *n_effective, float *scores, float *S_rows)
 {
     const int64_t words = (in + 31) / 32;
     const float A = 1.0f - alpha;
@@ -224,6 +226,7 @@ void oracle_ewma_select_literal_f32(const void *W, int64_t out, int64_t in, int6
                     den = FLT_EPSILON;
                 L = half_w2 / den;
             }
+            if (scores) scores[r * in + i] = L;
             if (i == 0)
                 est = L;
             float t = la * dev;
@@ -245,6 +248,7 @@ void oracle_ewma_select_literal_f32(const void *W, int64_t out, int64_t in, int6
             dev = b_dev + b_new;
         }
         if (row_pruned) row_pruned[r] = cnt;
+        if (S_rows) S_rows[r] = S_r;
     }
     if (n_effective) *n_effective = eff;
 }

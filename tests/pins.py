@@ -94,6 +94,22 @@ def pin_closed_form(orc, L=None):
         _, est32, dev32 = orc.ewma_row(Lrow, alpha, beta, la, precision="f32", L=L)
         assert np.allclose(est32, e, rtol=2e-6), np.abs(est32 / e - 1).max()
         assert np.allclose(dev32, d, rtol=1e-5, atol=1e-7)
+    # the whole-layer walk in double: masks, counts and scores of a small matrix against the closed-form
+    # decisions on scores formed with numpy
+    out, n, alpha, beta, la = 5, 70, 0.125, 0.25, 0.4
+    W = rng.standard_normal((out, n)).astype(np.float32)
+    hr = 0.5 / (1.0 - rng.uniform(0, 0.4, n))
+    mask, cnt, sc = orc.ewma_select(W, hr, alpha, beta, la, precision="f64", want_scores=True, L=L)
+    ref_sc = W.astype(np.float64) ** 2 * hr
+    assert np.allclose(sc, ref_sc, rtol=1e-15)
+    keep = orc.unpack_mask(mask, n)
+    assert mask.shape == (out, 3) and np.all((mask[:, 2] >> (n - 64)) == 0)
+    for r in range(out):
+        e, d = closed_form_states(ref_sc[r], alpha, beta)
+        thr = np.concatenate([[ref_sc[r, 0]], e[:-1]]) - la * np.concatenate([[0.0], d[:-1]])
+        assert (np.abs(ref_sc[r] - thr)[1:] > 1e-9 * np.abs(thr[1:])).all()
+        assert np.array_equal(~keep[r], ref_sc[r] < thr), r
+        assert cnt[r] == int((ref_sc[r] < thr).sum())
 
 
 def pin_constant_row(orc, L=None):
@@ -340,6 +356,17 @@ def pin_nm_invariants(orc, L=None):
                 order = np.lexsort((idx[r, j], g[r, j]))               # by score, then index
                 ref[r, j, order[: m - nk]] = False
         assert np.array_equal(keep, ref), (nk, m)
+        # the double-precision instantiation: same rule on double scores (per-group lexsort again)
+        hr64 = hr.astype(np.float64) * (1.0 + 1e-9 * np.arange(96))      # not representable in float
+        mask64, sc64 = orc.nm_select(Wb, hr64, nk, m, precision="f64", want_scores=True, L=L)
+        w64 = synth.bf16_bits_to_f32(Wb).astype(np.float64)
+        assert np.allclose(sc64, w64 * w64 * hr64, rtol=1e-15)
+        g64 = sc64.reshape(16, 96 // m, m)
+        ref64 = np.ones_like(keep)
+        for r in range(16):
+            for j in range(96 // m):
+                ref64[r, j, np.lexsort((idx[r, j], g64[r, j]))[: m - nk]] = False
+        assert np.array_equal(orc.unpack_mask(mask64, 96).reshape(16, 96 // m, m), ref64), (nk, m)
     # ties: all-equal weights, equal energies -> the first M-N of each group go
     X = np.ones((4, 16), dtype=np.float32)
     _, _, hr1 = orc.layer_stats(X, L=L)
@@ -362,9 +389,25 @@ def pin_channel_energy_changes_ranking(orc, L=None):
     assert np.allclose(sc[0], [6 / 11, 1.44 * 6 / 11, 1.62, 1.21 * 6 / 11], rtol=1e-6)
 
 
+def _literal_golden():
+    params, rows = None, []
+    with open(os.path.join(GOLDEN, "literal_worked_row.txt")) as fh:
+        for line in fh:
+            line = line.split("#")[0].strip()
+            if not line:
+                continue
+            tok = line.split()
+            if tok[0] == "params":
+                params = tuple(float(x) for x in tok[1:5])
+            else:
+                rows.append([float(x) for x in tok])
+    return params, np.array(rows)
+
+
 def pin_literal_form(orc, L=None):
     """Algorithm 1 as printed (S shrinks by w^2 on pruning) vs the fixed-S form: identical for
-    calibration-sized sums, different when S is comparable to w^2."""
+    calibration-sized sums, different when S is comparable to w^2; and a hand-worked row
+    (tests/golden/literal_worked_row.txt) that fixes the direction, the amount and the timing of the update."""
     from paper_2501_16376_amd import synth
     W, X = synth.config1()
     xsq, S, hr = orc.layer_stats(X, L=L)
@@ -378,6 +421,30 @@ def pin_literal_form(orc, L=None):
     m2, _, _ = orc.ewma_select(W, hr_s, 0.125, 0.125, 0.5, L=L)
     m3, _, eff3 = orc.ewma_select_literal(W, xsq_s, S_s, 0.125, 0.125, 0.5, L=L)
     assert eff3 > 1000 and not np.array_equal(m2, m3)
+
+    # the hand-worked row, twice (two rows of one matrix: every row starts again from S)
+    (alpha, beta, la, S0), g = _literal_golden()
+    n = g.shape[0]
+    Wg = np.ascontiguousarray(np.tile(g[:, 0].astype(np.float32), (2, 1)))
+    xg = g[:, 1].astype(np.float32)
+    mask, cnt, eff, sc, S_rows = orc.ewma_select_literal(Wg, xg, S0, alpha, beta, la, details=True, L=L)
+    keep = orc.unpack_mask(mask, n)
+    for r in range(2):
+        assert np.array_equal(sc[r].astype(np.float64), g[:, 3]), (r, sc[r])
+        assert np.array_equal(~keep[r], g[:, 5].astype(bool)), (r, keep[r])
+        assert float(S_rows[r]) == g[-1, 8], S_rows
+    assert cnt.tolist() == [int(g[:, 5].sum())] * 2
+    assert eff == 2 * int(np.sum(g[:, 8] != g[:, 2]))
+    # the table's own bookkeeping: S_r moves exactly when an element is pruned, by exactly w^2
+    assert np.array_equal(g[:, 2] - g[:, 8], g[:, 5] * g[:, 0] ** 2)
+    assert np.array_equal(g[1:, 2], g[:-1, 8]) and g[0, 2] == S0
+    # est / dev columns of the table follow from its scores through the fixed-S walk (pinned separately)
+    prune_w, est_w, dev_w = orc.ewma_row(g[:, 3], alpha, beta, la, precision="f32", L=L)
+    assert np.array_equal(est_w.astype(np.float64), g[:, 6]) and np.array_equal(dev_w.astype(np.float64), g[:, 7])
+    assert np.array_equal(prune_w.astype(bool), g[:, 5].astype(bool))
+    # and on this row holding S fixed gives other scores (the row exists to tell the two apart)
+    hr_fixed = orc.channel_factor_f32(xg, S0, L=L)
+    assert not np.array_equal(orc.score(Wg, hr_fixed, L=L)[0], sc[0])
 
 
 def pin_apply(orc, L=None):
@@ -427,6 +494,20 @@ def pin_sort_comparator(orc, L=None):
     return report
 
 
+def rng_weights_with_nan():
+    """2 x 32 float32 weights with a few NaNs of different payloads and signs, and infinities."""
+    W = _rng(41).standard_normal((2, 32)).astype(np.float32)
+    bits = W.view(np.uint32)
+    bits[0, 5] = 0x7fc00001
+    bits[0, 9] = 0xffc00000          # negative quiet NaN
+    bits[0, 17] = 0x7f800001         # smallest payload
+    bits[0, 2] = 0x7f800000          # +inf: squared it stays +inf and ranks below the NaNs
+    bits[1, 0] = 0x7fffffff
+    bits[1, 31] = 0x7fc00000
+    bits[1, 30] = 0xff800000         # -inf -> score +inf
+    return W
+
+
 def pin_topk_is_library_sort(orc, L=None):
     """The sort-based comparator equals numpy's lexsort on (score, index): the k smallest go, ties by
     the lower index, k = 0 and k = in behave, per-row k is honoured."""
@@ -449,6 +530,19 @@ def pin_topk_is_library_sort(orc, L=None):
     keep4 = orc.unpack_mask(orc.topk_select(Wb, hr, 40, L=L), 96)
     assert np.array_equal(keep4[4], np.arange(96) >= 40)          # all-tie row: the first 40 go
     assert np.all((~keep4).sum(1) == 40)
+    # NaN scores rank above every number, +inf included, and among themselves in index order whatever
+    # their payload: the same as sorting on (is-NaN, score, index)
+    Wn = rng_weights_with_nan()
+    hr1 = np.ones(Wn.shape[1], dtype=np.float32)
+    scn = Wn.astype(np.float64) ** 2
+    for k in (3, 20, 27, 28, 29, 30, 31, 32):
+        keepn = orc.unpack_mask(orc.topk_select(Wn, hr1, k, L=L), Wn.shape[1])
+        for r in range(Wn.shape[0]):
+            isn = np.isnan(scn[r])
+            order = np.lexsort((np.arange(Wn.shape[1]), np.where(isn, 0.0, scn[r]), isn))
+            ref = np.ones(Wn.shape[1], dtype=bool)
+            ref[order[:k]] = False
+            assert np.array_equal(keepn[r], ref), (k, r)
 
 
 def pin_compact_nm(orc, L=None):
