@@ -91,6 +91,24 @@ int swiftprune_layer_stats(const void *X, int64_t tokens, int64_t in, int64_t ld
                            void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * swiftprune_layer_stats for callers that cannot allocate device memory or have none to spare for a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, kernels and results as swiftprune_layer_stats, without `workspace`: the partial sums
+ * live in a device array of SP_STATIC_WORKSPACE_BYTES that is part of the library's code object (every
+ * GPU the library runs on holds its own copy until the process ends).  The call allocates and frees
+ * nothing.  Shapes with swiftprune_stats_workspace_bytes(tokens, in) > SP_STATIC_WORKSPACE_BYTES are
+ * refused with SP_ENOSPC (nothing is enqueued); all Llama / Pythia layer widths at 262144 tokens need
+ * about 2 MB.  The device of `hip_stream` must be the current device.
+ * All calls on one GPU share that GPU's array: two calls whose kernels may overlap (different streams
+ * without an ordering between them, or host threads) race and give wrong sums; calls on one stream, or
+ * otherwise ordered, are safe.  Nothing has to be cleared between calls.
+ */
+#define SP_STATIC_WORKSPACE_BYTES ((size_t)8 << 20)
+int swiftprune_layer_stats_static(const void *X, int64_t tokens, int64_t in, int64_t ldx, sp_dtype dt,
+                                  float *xsq, float *S, float *hr, int accumulate, int finalize,
+                                  void *hip_stream);
+
+/*
  * The last part of step 1 on its own (denominator of the Sec. 3.1 score equation):
  *     hr[q] = 1/2 / (1 - xsq[q]/S),  with the conventions of swiftprune_layer_stats for S == 0 and a
  *     non-positive denominator.

@@ -18,7 +18,7 @@ SP_F32, SP_BF16, SP_F16 = 0, 1, 2
 SP_OK, SP_EINVAL, SP_ENOSPC, SP_EHIP, SP_ERANGE = 0, -1, -2, -3, -4
 SP_SEQUENTIAL_ORDER, SP_APPLY_INPLACE = 1, 2
 
-EXPORTS = ("swiftprune_layer_stats", "swiftprune_score_select", "swiftprune_nm_select",
+EXPORTS = ("swiftprune_layer_stats", "swiftprune_layer_stats_static", "swiftprune_score_select", "swiftprune_nm_select",
            "swiftprune_apply", "swiftprune_channel_factor", "swiftprune_ewma_trace", "swiftprune_count_pruned", "swiftprune_calibrate_la", "swiftprune_topk_select", "swiftprune_compact_nm", "swiftprune_expand_nm", "swiftprune_nm_meta_words", "swiftprune_la_for_sparsity", "swiftprune_stats_workspace_bytes",
            "swiftprune_strerror", "swiftprune_version")
 
@@ -49,6 +49,8 @@ def load_library(path: str | None = None) -> C.CDLL:
     vp, i64, i32, u32, f = C.c_void_p, C.c_int64, C.c_int, C.c_uint32, C.c_float
     L.swiftprune_layer_stats.argtypes = [vp, i64, i64, i64, i32, vp, vp, vp, i32, i32, vp, C.c_size_t, vp]
     L.swiftprune_layer_stats.restype = i32
+    L.swiftprune_layer_stats_static.argtypes = [vp, i64, i64, i64, i32, vp, vp, vp, i32, i32, vp]
+    L.swiftprune_layer_stats_static.restype = i32
     L.swiftprune_score_select.argtypes = [vp, i64, i64, i64, i32, vp, f, C.POINTER(sp_ewma_params),
                                           vp, vp, vp, u32, vp]
     L.swiftprune_score_select.restype = i32
@@ -163,6 +165,17 @@ def swiftprune_layer_stats(X, xsq, S, hr, accumulate: bool = False, finalize: bo
         workspace.numel() * workspace.element_size(), _stream(stream))
     _check(code, "swiftprune_layer_stats")
     return workspace
+
+
+def swiftprune_layer_stats_static(X, xsq, S, hr, accumulate: bool = False, finalize: bool = True, stream=None):
+    """swiftprune_layer_stats with the partial sums in the library's own device array (no workspace)."""
+    import torch
+    ptr, tokens, n_in, ldx, dt = _matrix(X)
+    code = load_library().swiftprune_layer_stats_static(
+        ptr, tokens, n_in, ldx, dt, _vec(xsq, torch.float32, n_in, "xsq"),
+        _vec(S, torch.float32, 1, "S"), _vec(hr, torch.float32, n_in, "hr"),
+        int(bool(accumulate)), int(bool(finalize)), _stream(stream))
+    _check(code, "swiftprune_layer_stats_static")
 
 
 def swiftprune_channel_factor(xsq, S, hr, stream=None):
