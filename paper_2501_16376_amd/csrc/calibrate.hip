@@ -1,7 +1,6 @@
-// Threshold calibration for the EWMA selection rule.  The paper ties the pruning
-// ratio to the multiplier la by a five-entry table (Sec. 3.1, "parameter
-// adjustment under different pruning ratios") and says la "can be tuned for
-// different levels of sparsity"; other ratios need a search.  With S held fixed
+// Threshold calibration for the EWMA selection rule.  Sec. 3.1 lists the multiplier
+// la for five pruning ratios (50 % to 90 %) and leaves every other ratio to tuning
+// la; the appendix reports ratios of 10-40 % without their la.  With S held fixed
 // est and dev do not depend on la, so one pass over W can count the pruned
 // weights for many candidate la at once, and the pruned fraction is monotone
 // non-increasing in la.  The search below brackets the target ratio with 16

@@ -44,6 +44,10 @@ EwmaConsts make_ewma_consts(float alpha, float beta, float la);
 hipError_t launch_ewma_scan(const void* W, int64_t out, int64_t in, int64_t ldw, int dt, bool vec,
                             const float* hr, const EwmaConsts& c, uint32_t* keep_mask,
                             int32_t* row_pruned, float* scores, bool apply, hipStream_t stream);
+// fast path for the 16-byte-vector layout and alpha < 1; team = wavefronts per row (1, 2, 4; 0 = by row count)
+hipError_t launch_ewma_team(const void* W, int64_t out, int64_t in, int64_t ldw, int dt, const float* hr,
+                            const EwmaConsts& c, uint32_t* keep_mask, int32_t* row_pruned, bool apply,
+                            int team, hipStream_t stream);
 hipError_t launch_ewma_sequential(const void* W, int64_t out, int64_t in, int64_t ldw, int dt,
                                   const float* hr, float alpha, float beta, float la,
                                   uint32_t* keep_mask, int32_t* row_pruned, float* scores, bool apply,

@@ -155,6 +155,179 @@ __global__ __launch_bounds__(kColThreads) void apply_kernel(void* __restrict__ W
     }
 }
 
+// ---------------------------------------------------------------------------
+// Band variants for the 16-byte-vector path.  In-place read-modify-write streams
+// run fastest on this part when the whole device walks ONE contiguous window in
+// lock step (a few workgroups per compute unit, non-temporal loads and stores)
+// instead of every workgroup owning a region of its own.  The columns are cut
+// into strips of at most 256 chunks (one chunk of 8 columns per lane, fixed for
+// the lifetime of the lane, so its channel factors are loaded once) and the
+// rows into batches of U consecutive rows dealt round-robin to the `splits`
+// workgroups of a strip: at any moment all workgroups together read, and then
+// rewrite, splits*U consecutive rows.  grid = (nstrips, splits), block = 256.
+// ---------------------------------------------------------------------------
+struct BandPlan {
+    int strip_units;  // chunks of 8 columns per strip (multiple of 8, <= 256)
+    int nstrips;
+    int splits;
+    int unroll;       // rows per batch
+};
+
+BandPlan make_band_plan(int64_t out, int64_t in, int target_groups, int unroll = 4) {
+    BandPlan p;
+    const int64_t units = (in + 7) / 8;
+    int64_t nstrips = (units + kColThreads - 1) / kColThreads;
+    int64_t su = ((units + nstrips - 1) / nstrips + 7) / 8 * 8;
+    if (su > kColThreads) su = kColThreads;
+    nstrips = (units + su - 1) / su;
+    p.strip_units = (int)su;
+    p.nstrips = (int)nstrips;
+    p.unroll = unroll;
+    int64_t splits = target_groups / nstrips;
+    // small matrices: fewer rows per batch before fewer workgroups
+    while (p.unroll > 1 && (out + p.unroll - 1) / p.unroll < splits) p.unroll >>= 1;
+    const int64_t batches = (out + p.unroll - 1) / p.unroll;
+    if (splits > batches) splits = batches;
+    if (splits < 1) splits = 1;
+    p.splits = (int)splits;
+    return p;
+}
+
+template <int DT, int M, int U>
+__global__ __launch_bounds__(kColThreads) void nm_select_band_kernel(
+    void* __restrict__ W, int64_t out, int64_t in, int64_t ldw, const float* __restrict__ hr,
+    int n_prune, uint32_t* __restrict__ keep_mask, float* __restrict__ scores, int apply,
+    int strip_units) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t unit = (int64_t)blockIdx.x * strip_units + threadIdx.x;
+    const int64_t q0 = unit * 8;
+    const bool active = (int)threadIdx.x < strip_units && q0 < in;  // in % 8 == 0 on this path
+    const int64_t mask_words = (in + 31) >> 5;
+    const int64_t step = (int64_t)gridDim.y * U;
+
+    Factor8 f;
+    if (active) f.load_vec(hr, q0); else f.load_elems(hr, 0, 0);
+
+    auto fetch = [&](Chunk8<DT>* w, int64_t r0) {
+#pragma unroll
+        for (int j = 0; j < U; ++j) {
+            if (active && r0 + j < out) w[j].load_vec(W, (r0 + j) * ldw + q0); else w[j].zero();
+        }
+    };
+    auto work = [&](Chunk8<DT>* w, int64_t r0) {
+#pragma unroll
+        for (int j = 0; j < U; ++j) {
+            const int64_t row = r0 + j;
+            if (row >= out) break;  // uniform over the workgroup
+            float L[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) L[k] = score_of(w[j].get(k), f.v[k]);
+            uint32_t keep = (M == 16) ? nm_keep_bits16(L, n_prune, lane) : nm_keep_bits<(M == 16 ? 8 : M)>(L, n_prune);
+            if (!active) keep = 0u;
+            if (scores != nullptr && active) store8(scores + row * in + q0, L, true, 8);
+            const uint32_t word = quad_gather_bytes(keep, lane);
+            if ((lane & 3) == 0 && active) keep_mask[row * mask_words + (q0 >> 5)] = word;
+            if (apply && active) {
+                w[j].apply(keep);
+                w[j].store_vec_nt(W, row * ldw + q0);
+            }
+        }
+    };
+    // two batches alternate: while one is worked on, the loads of the next are in flight
+    Chunk8<DT> a[U], b[U];
+    int64_t r0 = (int64_t)blockIdx.y * U;
+    fetch(a, r0);
+    while (r0 < out) {
+        fetch(b, r0 + step);
+        work(a, r0);
+        r0 += step;
+        if (r0 >= out) break;
+        fetch(a, r0 + step);
+        work(b, r0);
+        r0 += step;
+    }
+}
+
+template <int DT, int U>
+__global__ __launch_bounds__(kColThreads) void apply_band_kernel(void* __restrict__ W, int64_t out, int64_t in,
+                                                                int64_t ldw,
+                                                                const uint32_t* __restrict__ keep_mask,
+                                                                int strip_units) {
+    const int64_t unit = (int64_t)blockIdx.x * strip_units + threadIdx.x;
+    const int64_t q0 = unit * 8;
+    if ((int)threadIdx.x >= strip_units || q0 >= in) return;
+    const int64_t mask_words = (in + 31) >> 5;
+    const int64_t step = (int64_t)gridDim.y * U;
+    const int shift = (int)(q0 & 31);
+
+    auto fetch = [&](Chunk8<DT>* w, uint32_t* keep, int64_t r0) {
+#pragma unroll
+        for (int j = 0; j < U; ++j) {
+            if (r0 + j < out) {
+                w[j].load_vec(W, (r0 + j) * ldw + q0);
+                keep[j] = keep_mask[(r0 + j) * mask_words + (q0 >> 5)];
+            }
+        }
+    };
+    auto work = [&](Chunk8<DT>* w, uint32_t* keep, int64_t r0) {
+#pragma unroll
+        for (int j = 0; j < U; ++j) {
+            if (r0 + j < out) {
+                w[j].apply((keep[j] >> shift) & 0xffu);
+                w[j].store_vec_nt(W, (r0 + j) * ldw + q0);
+            }
+        }
+    };
+    Chunk8<DT> a[U], b[U];
+    uint32_t ka[U], kb[U];
+    int64_t r0 = (int64_t)blockIdx.y * U;
+    fetch(a, ka, r0);
+    while (r0 < out) {
+        fetch(b, kb, r0 + step);
+        work(a, ka, r0);
+        r0 += step;
+        if (r0 >= out) break;
+        fetch(a, ka, r0 + step);
+        work(b, kb, r0);
+        r0 += step;
+    }
+}
+
+// Workgroups of a band launch, from sweeps on MI355X (bf16, 1024 ... 14336 rows x 4096 ... 14336 columns):
+// the plain apply stream is best with two workgroups per compute unit, the selection kernels, which do
+// ~100 VALU instructions per 16-byte load, need three to hide them.  Four rows per batch, two batches alternating.
+constexpr int kApplyBandGroups = 512;
+constexpr int kSelectBandGroups = 768;
+
+template <int DT, int M>
+static hipError_t launch_nm_band(void* W, int64_t out, int64_t in, int64_t ldw, const float* hr, int n_prune,
+                                 uint32_t* keep_mask, float* scores, int apply, int target_groups,
+                                 hipStream_t stream, int unroll = 4) {
+    const BandPlan p = make_band_plan(out, in, target_groups, unroll);
+    const dim3 grid((unsigned)p.nstrips, (unsigned)p.splits), block(kColThreads);
+    switch (p.unroll) {
+        case 8: hipLaunchKernelGGL((nm_select_band_kernel<DT, M, 8>), grid, block, 0, stream, W, out, in, ldw, hr, n_prune, keep_mask, scores, apply, p.strip_units); break;
+        case 4: hipLaunchKernelGGL((nm_select_band_kernel<DT, M, 4>), grid, block, 0, stream, W, out, in, ldw, hr, n_prune, keep_mask, scores, apply, p.strip_units); break;
+        case 2: hipLaunchKernelGGL((nm_select_band_kernel<DT, M, 2>), grid, block, 0, stream, W, out, in, ldw, hr, n_prune, keep_mask, scores, apply, p.strip_units); break;
+        default: hipLaunchKernelGGL((nm_select_band_kernel<DT, M, 1>), grid, block, 0, stream, W, out, in, ldw, hr, n_prune, keep_mask, scores, apply, p.strip_units); break;
+    }
+    return hipGetLastError();
+}
+
+template <int DT>
+static hipError_t launch_apply_band(void* W, int64_t out, int64_t in, int64_t ldw, const uint32_t* keep_mask,
+                                    int target_groups, hipStream_t stream, int unroll = 4) {
+    const BandPlan p = make_band_plan(out, in, target_groups, unroll);
+    const dim3 grid((unsigned)p.nstrips, (unsigned)p.splits), block(kColThreads);
+    switch (p.unroll) {
+        case 8: hipLaunchKernelGGL((apply_band_kernel<DT, 8>), grid, block, 0, stream, W, out, in, ldw, keep_mask, p.strip_units); break;
+        case 4: hipLaunchKernelGGL((apply_band_kernel<DT, 4>), grid, block, 0, stream, W, out, in, ldw, keep_mask, p.strip_units); break;
+        case 2: hipLaunchKernelGGL((apply_band_kernel<DT, 2>), grid, block, 0, stream, W, out, in, ldw, keep_mask, p.strip_units); break;
+        default: hipLaunchKernelGGL((apply_band_kernel<DT, 1>), grid, block, 0, stream, W, out, in, ldw, keep_mask, p.strip_units); break;
+    }
+    return hipGetLastError();
+}
+
 template <int DT, bool VEC>
 static hipError_t launch_nm_t(const void* W, int64_t out, int64_t in, int64_t ldw, const float* hr,
                               int n_keep, int m_group, uint32_t* keep_mask, float* scores, bool apply,
@@ -192,8 +365,17 @@ hipError_t launch_nm_select(const void* W, int64_t out, int64_t in, int64_t ldw,
                             float* scores, bool apply, hipStream_t stream) {
     return with_dtype(dt, [&](auto tag) {
         constexpr int DT = decltype(tag)::value;
-        return vec ? launch_nm_t<DT, true>(W, out, in, ldw, hr, n_keep, m_group, keep_mask, scores, apply, stream)
-                   : launch_nm_t<DT, false>(W, out, in, ldw, hr, n_keep, m_group, keep_mask, scores, apply, stream);
+        if (vec) {
+            void* Wm = const_cast<void*>(W);
+            const int n_prune = m_group - n_keep, ap = apply ? 1 : 0;
+            switch (m_group) {
+                case 4: return launch_nm_band<DT, 4>(Wm, out, in, ldw, hr, n_prune, keep_mask, scores, ap, kSelectBandGroups, stream);
+                case 8: return launch_nm_band<DT, 8>(Wm, out, in, ldw, hr, n_prune, keep_mask, scores, ap, kSelectBandGroups, stream);
+                case 16: return launch_nm_band<DT, 16>(Wm, out, in, ldw, hr, n_prune, keep_mask, scores, ap, kSelectBandGroups, stream);
+                default: return hipErrorInvalidValue;
+            }
+        }
+        return launch_nm_t<DT, false>(W, out, in, ldw, hr, n_keep, m_group, keep_mask, scores, apply, stream);
     });
 }
 
@@ -203,12 +385,12 @@ hipError_t launch_apply(void* W, int64_t out, int64_t in, int64_t ldw, int dt, b
     const unsigned col_tiles = (unsigned)((chunks + kWave - 1) / kWave);
     const int64_t tiles = (int64_t)col_tiles * ((out + kRows - 1) / kRows);
     const int64_t groups = (tiles + kColThreads / kWave - 1) / (kColThreads / kWave);
-    if (groups > 0x7fffffff) return hipErrorInvalidValue;
+    if (!vec && groups > 0x7fffffff) return hipErrorInvalidValue;
     dim3 grid((unsigned)groups);
     return with_dtype(dt, [&](auto tag) {
         constexpr int DT = decltype(tag)::value;
-        if (vec) hipLaunchKernelGGL((apply_kernel<DT, true>), grid, dim3(kColThreads), 0, stream, W, out, in, ldw, keep_mask, col_tiles);
-        else hipLaunchKernelGGL((apply_kernel<DT, false>), grid, dim3(kColThreads), 0, stream, W, out, in, ldw, keep_mask, col_tiles);
+        if (vec) return launch_apply_band<DT>(W, out, in, ldw, keep_mask, kApplyBandGroups, stream);
+        hipLaunchKernelGGL((apply_kernel<DT, false>), grid, dim3(kColThreads), 0, stream, W, out, in, ldw, keep_mask, col_tiles);
         return hipGetLastError();
     });
 }

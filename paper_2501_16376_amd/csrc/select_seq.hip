@@ -1,12 +1,36 @@
-// Steps 2+3 of the SwiftPrune layer path in strict sequential order: one lane
-// walks one row element by element, executing the statements of Algorithm 1's
-// loop body in the order they are written, every operation rounded on its own
-// (no fused multiply-add).  It exists to reproduce a sequential fp32 evaluation
-// bit for bit; the scan kernel is the fast path.
+// Steps 2+3 of the SwiftPrune layer path in strict sequential order (Sec. 3.2;
+// Algorithm 1 loop; state-update table of Sec. 3.1): one lane owns one row and
+// consumes it one 32-column mask word at a time.  For every word it first forms
+// the 32 scores (loads hoisted ahead of the dependent chain), then threads the
+// (est, dev) state through them with every operation rounded on its own - no
+// fused multiply-add, no reassociation - so the result is the sequential fp32
+// evaluation bit for bit.  It exists for validation; the scan kernel is the
+// fast path.
 #include "common.hpp"
 #include "kernels.hpp"
 
 namespace sp {
+
+// (est, dev) of one row, in fp32, advanced one score at a time.
+struct StrictWalk {
+    float est, dev;
+    float keep_est, keep_dev;  // 1 - alpha, 1 - beta
+    float alpha, beta, la;
+
+    __device__ __forceinline__ StrictWalk(float a, float b, float l)
+        : est(0.f), dev(0.f), keep_est(__fsub_rn(1.0f, a)), keep_dev(__fsub_rn(1.0f, b)), alpha(a), beta(b), la(l) {}
+
+    // the test uses the state as it stands before the score is absorbed
+    __device__ __forceinline__ bool below_threshold(float score) const {
+        return score < __fsub_rn(est, __fmul_rn(la, dev));
+    }
+    // est first, then dev from the new est
+    __device__ __forceinline__ void absorb(float score) {
+        est = __fadd_rn(__fmul_rn(keep_est, est), __fmul_rn(alpha, score));
+        const float gap = fabsf(__fsub_rn(est, score));
+        dev = __fadd_rn(__fmul_rn(keep_dev, dev), __fmul_rn(beta, gap));
+    }
+};
 
 template <int DT>
 __global__ __launch_bounds__(64) void ewma_sequential_kernel(
@@ -15,39 +39,37 @@ __global__ __launch_bounds__(64) void ewma_sequential_kernel(
     int32_t* __restrict__ row_pruned, float* __restrict__ scores, int apply) {
     const int64_t row = (int64_t)blockIdx.x * 64 + threadIdx.x;
     if (row >= out) return;
-    const int64_t mask_words = (in + 31) >> 5;
-    const float A = __fsub_rn(1.0f, alpha);
-    const float B = __fsub_rn(1.0f, beta);
-    float est = 0.f, dev = 0.f;
-    int pruned = 0;
-    uint32_t word = 0u;
-    for (int64_t q = 0; q < in; ++q) {
-        const float w = load_scalar<DT>(W, row * ldw + q);
-        const float L = score_of(w, hr[q]);
-        if (scores != nullptr) scores[row * in + q] = L;
-        if (q == 0) est = L;
-        const float t = __fmul_rn(la, dev);
-        const float thr = __fsub_rn(est, t);
-        const bool prune = L < thr;
-        const float a_est = __fmul_rn(A, est);
-        const float a_new = __fmul_rn(alpha, L);
-        est = __fadd_rn(a_est, a_new);
-        const float diff = __fsub_rn(est, L);
-        const float b_dev = __fmul_rn(B, dev);
-        const float b_new = __fmul_rn(beta, fabsf(diff));
-        dev = __fadd_rn(b_dev, b_new);
-        if (prune) {
-            ++pruned;
-            if (apply) store_zero<DT>(W, row * ldw + q);
-        } else {
-            word |= 1u << (q & 31);
+    const int64_t words = (in + 31) >> 5;
+    const int64_t w_row = row * ldw;
+    StrictWalk walk(alpha, beta, la);
+    int gone = 0;
+
+    for (int64_t word = 0; word < words; ++word) {
+        const int64_t q0 = word << 5;
+        const int live = (int)min((int64_t)32, in - q0);
+        float score[32];
+#pragma unroll
+        for (int b = 0; b < 32; ++b)
+            score[b] = b < live ? score_of(load_scalar<DT>(W, w_row + q0 + b), hr[q0 + b]) : 0.f;
+        if (scores != nullptr)
+            for (int b = 0; b < live; ++b) scores[row * in + q0 + b] = score[b];
+        if (word == 0) walk.est = score[0];  // the walk starts at the row's first score, dev at 0
+
+        uint32_t drop = 0u;
+#pragma unroll
+        for (int b = 0; b < 32; ++b) {
+            if (b < live) {
+                drop |= walk.below_threshold(score[b]) ? (1u << b) : 0u;
+                walk.absorb(score[b]);
+            }
         }
-        if ((q & 31) == 31 || q == in - 1) {
-            keep_mask[row * mask_words + (q >> 5)] = word;
-            word = 0u;
-        }
+        const uint32_t live_bits = live == 32 ? 0xffffffffu : ((1u << live) - 1u);
+        keep_mask[row * words + word] = ~drop & live_bits;
+        gone += __popc(drop);
+        if (apply)
+            for (uint32_t d = drop; d != 0u; d &= d - 1u) store_zero<DT>(W, w_row + q0 + (__ffs(d) - 1));
     }
-    if (row_pruned != nullptr) row_pruned[row] = pruned;
+    if (row_pruned != nullptr) row_pruned[row] = gone;
 }
 
 hipError_t launch_ewma_sequential(const void* W, int64_t out, int64_t in, int64_t ldw, int dt,

@@ -16,8 +16,9 @@ constexpr int kTopkThreads = 256;
 template <int DT>
 __device__ __forceinline__ uint32_t score_key(const void* W, int64_t idx, float factor) {
     const float L = score_of(load_scalar<DT>(W, idx), factor);
-    // scores are >= +0 (or NaN): the bit pattern orders them; NaN sorts above +inf
-    return __float_as_uint(L) & 0x7fffffffu;
+    // scores are >= +0 (or NaN): the bit pattern orders them.  Every NaN gets the one key above +inf, so
+    // that NaNs rank after all numbers and among themselves in index order, whatever their payload
+    return L != L ? 0x7fffffffu : (__float_as_uint(L) & 0x7fffffffu);
 }
 
 // exclusive prefix sum of one int per thread over 256 threads; also returns the total

@@ -61,3 +61,17 @@ def check_ewma_mask(orc, W_host, hr, alpha, beta, la, mask_gpu, cnt_gpu=None):
         same[list(per_row.keys())] = False
         assert np.array_equal(np.asarray(cnt_gpu)[same], cnt_o[same])
     return len(diffs)
+
+
+def near_threshold_count(orc, W_host, hr, alpha, beta, la):
+    """How many decisions of the whole matrix the rounding-level rule leaves open: elements (other than a
+    row's first) whose oracle score lies within TOL (relative) of the oracle's threshold for them."""
+    total = 0
+    sc = orc.score(np.ascontiguousarray(W_host), hr)
+    for r in range(W_host.shape[0]):
+        L = sc[r]
+        _, est, dev = orc.ewma_row(L, alpha, beta, la, precision="f32")
+        thr = est[:-1] - np.float32(la) * dev[:-1]
+        scale = np.maximum(np.abs(L[1:]), np.abs(thr))
+        total += int(np.sum(np.abs(L[1:].astype(np.float64) - thr.astype(np.float64)) <= TOL * scale))
+    return total

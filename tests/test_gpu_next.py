@@ -35,10 +35,12 @@ def _inputs(orc, gpu, out, n, tokens, seed, dtype="bf16"):
 
 @pytest.mark.parametrize("out,n,dtype", [(200, 2048, "bf16"), (37, 1000, "bf16"), (64, 777, "f32"), (50, 1536, "f16")])
 def test_count_pruned_matches_oracle(orc, gpu, out, n, dtype):
-    """Counts for 16 (and for 3) candidate la in one pass equal the oracle's totals, up to the few
-    decisions the scan path may flip at the rounding level."""
+    """Counts for 16 (and for 3) candidate la in one pass equal the oracle's totals; a total may be off by
+    at most the number of decisions the rounding-level rule leaves open at that la (scores within 1e-5
+    relative of their threshold, counted with the oracle)."""
     import torch
     from paper_2501_16376_amd import binding as b
+    from gpu_util import near_threshold_count
     say(f"[case] count_pruned out={out} in={n} {dtype}")
     Wh, hr, W, hr_dev = _inputs(orc, gpu, out, n, 256, seed=out + n, dtype=dtype)
     for las in (list(np.linspace(-2.0, 2.0, 16)), [0.5, -0.9, 4.0]):
@@ -47,7 +49,9 @@ def test_count_pruned_matches_oracle(orc, gpu, out, n, dtype):
         torch.cuda.synchronize()
         got = counts.cpu().numpy()
         ref = np.array([int(orc.ewma_select(Wh, hr, A, B, float(np.float32(la)))[1].sum()) for la in las])
-        assert np.all(np.abs(got[:len(las)] - ref) <= 2), (got[:len(las)], ref)
+        slack = np.array([near_threshold_count(orc, Wh, hr, A, B, float(np.float32(la))) for la in las])
+        assert np.all(np.abs(got[:len(las)] - ref) <= slack), (got[:len(las)], ref, slack)
+        assert slack.max() <= 8                                     # and that is a handful, not a loophole
         assert np.all(got[len(las):] == -1)                         # untouched beyond n_la
         assert np.all(np.diff(got[:len(las)][np.argsort(las)]) <= 0)  # non-increasing in la
 
@@ -109,6 +113,24 @@ def test_topk_select_matches_sort(orc, gpu, out, n, dtype):
     torch.cuda.synchronize()
     ref = orc.apply(Wh.copy(), orc.topk_select(Wh, hr, n // 2))
     assert np.array_equal(synth.torch_to_host_bits(W2), ref)
+
+
+def test_topk_nan_scores_rank_last_in_index_order(orc, gpu):
+    """NaN scores (here from NaN weights of several payloads and signs) rank above every number, +inf
+    included, and among themselves by index: the masks equal the oracle's for every k around the boundary."""
+    import torch
+    from paper_2501_16376_amd import binding as b
+    from gpu_util import to_device, mask_to_host
+    import pins
+    Wh = np.ascontiguousarray(np.tile(pins.rng_weights_with_nan(), (3, 1)))        # 6 x 32 float32
+    n = Wh.shape[1]
+    hr = np.ones(n, dtype=np.float32)
+    W, hr_dev = to_device(Wh, gpu), to_device(hr, gpu)
+    mask = torch.empty((Wh.shape[0], 1), dtype=torch.int32, device=gpu)
+    for k in (0, 3, 20, 27, 28, 29, 30, 31, 32):
+        b.swiftprune_topk_select(W, hr_dev, mask, k_uniform=k)
+        torch.cuda.synchronize()
+        assert np.array_equal(mask_to_host(mask), orc.topk_select(Wh, hr, k)), k
 
 
 def test_ewma_vs_sort_overlap_at_scale(orc, gpu):

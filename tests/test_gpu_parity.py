@@ -114,6 +114,9 @@ def _layer_case(orc, gpu, out, n, tokens, dtype, seed, las=(0.5,), nms=((2, 4), 
         m_scan, c_scan, sc_scan = _select_gpu(W_dev, hr_dev, la, want_scores=True)
         assert np.array_equal(sc_scan.view(np.uint32), sc_o.view(np.uint32))
         tolerated += check_ewma_mask(orc, Wh, hr_o, A, B, la, m_scan, c_scan)
+        # --- the same call without the scores output: aligned layouts take the fast kernel here
+        m_fast, c_fast, _ = _select_gpu(W_dev, hr_dev, la)
+        tolerated += check_ewma_mask(orc, Wh, hr_o, A, B, la, m_fast, c_fast)
         # --- scan path on the GPU's own statistics (end to end)
         m_e2e, c_e2e, sc_e2e = _select_gpu(W_dev, to_device(hr_g, gpu), la, want_scores=True)
         assert np.allclose(sc_e2e, sc_o, rtol=1e-5, atol=0)
@@ -143,8 +146,10 @@ def _layer_case(orc, gpu, out, n, tokens, dtype, seed, las=(0.5,), nms=((2, 4), 
     W3 = W_dev.clone() if not pitch_pad else to_device(Wp, gpu)[:, :n]
     b.swiftprune_score_select(W3, hr_dev, mk, la=las[0], flags=b.SP_APPLY_INPLACE)
     torch.cuda.synchronize()
-    ref3 = orc.apply(Wh.copy(), mask_to_host(mk))
-    assert same_bits(synth.torch_to_host_bits(W3), ref3)      # fused apply agrees with its own mask
+    # the fused mask against the oracle's under the threshold rule, and the zeroed weights against the
+    # oracle's apply of that mask: together they tie the fused result to the oracle, not to itself
+    check_ewma_mask(orc, Wh, hr_o, A, B, las[0], mask_to_host(mk))
+    assert same_bits(synth.torch_to_host_bits(W3), orc.apply(Wh.copy(), mask_to_host(mk)))
     if n % 4 == 0:
         nm_o, _ = orc.nm_select(Wh, hr_o, 2, 4)
         W4 = W_dev.clone() if not pitch_pad else to_device(Wp, gpu)[:, :n]
@@ -178,6 +183,9 @@ def test_config1_fp32(orc, gpu):
     (300, 1376, 5000, "f16", 0),       # IEEE half storage: vector path
     (33, 1001, 777, "f16", 0),         # IEEE half, element-wise path
     (65, 1000, 300, "f16", 24),        # IEEE half, padded pitch
+    (1300, 4104, 64, "bf16", 0),       # two wavefronts per row, three spans, the last one ragged
+    (40, 9000, 64, "bf16", 0),         # four wavefronts per row, three spans, rows not a multiple of 4
+    (1100, 1032, 64, "f32", 8),        # two wavefronts per row, fp32, padded pitch
 ])
 def test_shapes(orc, gpu, out, n, tokens, dtype, pad):
     t = _layer_case(orc, gpu, out, n, tokens, dtype, seed=out + n, pitch_pad=pad,
