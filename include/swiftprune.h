@@ -149,6 +149,37 @@ int swiftprune_score_select(const void *W, int64_t out, int64_t in, int64_t ldw,
                             uint32_t flags, void *hip_stream);
 
 /*
+ * Several weight matrices that multiply the SAME layer input (q / k / v of an attention block, gate / up
+ * of an MLP) share the calibration statistics: Algorithm 1 forms S and the x_q^2 once from the input X,
+ * so one swiftprune_layer_stats call serves all of them.  The two calls below prune such a group in one
+ * launch: the rows of all matrices are spread over one grid, which also keeps a short matrix (1024
+ * rows) from occupying the device alone.  Results are identical to calling swiftprune_score_select /
+ * swiftprune_nm_select once per matrix with the same hr.
+ *
+ *   mats     host array of n_mats (1 .. SP_MAX_GROUP) descriptors; every matrix has `in` columns and
+ *            dtype dt; W, keep_mask, row_pruned are device pointers as in the single-matrix calls
+ *   others   as in swiftprune_score_select / swiftprune_nm_select (no scores output)
+ * Matrices that miss the fast layout (16-byte alignment, in % 8) or flags / parameters that need the
+ * general kernels (SP_SEQUENTIAL_ORDER, alpha == 1) are handled by one launch per matrix instead.
+ * SP_EINVAL if any descriptor is invalid; nothing is enqueued then.
+ */
+typedef struct {
+    void *W;              /* [out, in], pitch ldw */
+    int64_t out;
+    int64_t ldw;
+    uint32_t *keep_mask;  /* [out, (in+31)/32], fully overwritten */
+    int32_t *row_pruned;  /* nullable [out]; not used by the N:M call */
+} sp_matrix;
+#define SP_MAX_GROUP 8
+
+int swiftprune_score_select_group(const sp_matrix *mats, int n_mats, int64_t in, sp_dtype dt,
+                                  const float *hr, float sparsity, const sp_ewma_params *params,
+                                  uint32_t flags, void *hip_stream);
+int swiftprune_nm_select_group(const sp_matrix *mats, int n_mats, int64_t in, sp_dtype dt,
+                               const float *hr, int n_keep, int m_group, uint32_t flags,
+                               void *hip_stream);
+
+/*
  * Threshold tuning (Sec. 3.1: the ratio -> la table covers 50..90 % only, and la is described as the
  * knob that sets the level of sparsity).  With S fixed, est and dev do not depend on la, so one pass over W
  * counts the pruned weights for several candidate la at once.

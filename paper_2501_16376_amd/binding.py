@@ -19,7 +19,7 @@ SP_OK, SP_EINVAL, SP_ENOSPC, SP_EHIP, SP_ERANGE = 0, -1, -2, -3, -4
 SP_SEQUENTIAL_ORDER, SP_APPLY_INPLACE = 1, 2
 
 EXPORTS = ("swiftprune_layer_stats", "swiftprune_layer_stats_static", "swiftprune_score_select", "swiftprune_nm_select",
-           "swiftprune_apply", "swiftprune_channel_factor", "swiftprune_ewma_trace", "swiftprune_count_pruned", "swiftprune_calibrate_la", "swiftprune_topk_select", "swiftprune_compact_nm", "swiftprune_expand_nm", "swiftprune_nm_meta_words", "swiftprune_la_for_sparsity", "swiftprune_stats_workspace_bytes",
+           "swiftprune_apply", "swiftprune_score_select_group", "swiftprune_nm_select_group", "swiftprune_channel_factor", "swiftprune_ewma_trace", "swiftprune_count_pruned", "swiftprune_calibrate_la", "swiftprune_topk_select", "swiftprune_compact_nm", "swiftprune_expand_nm", "swiftprune_nm_meta_words", "swiftprune_la_for_sparsity", "swiftprune_stats_workspace_bytes",
            "swiftprune_strerror", "swiftprune_version")
 
 
@@ -31,6 +31,14 @@ class SwiftPruneError(RuntimeError):
 
 class sp_ewma_params(C.Structure):
     _fields_ = [("alpha", C.c_float), ("beta", C.c_float), ("la", C.c_float)]
+
+
+class sp_matrix(C.Structure):
+    _fields_ = [("W", C.c_void_p), ("out", C.c_int64), ("ldw", C.c_int64), ("keep_mask", C.c_void_p),
+                ("row_pruned", C.c_void_p)]
+
+
+SP_MAX_GROUP = 8
 
 
 _lib = None
@@ -54,6 +62,11 @@ def load_library(path: str | None = None) -> C.CDLL:
     L.swiftprune_score_select.argtypes = [vp, i64, i64, i64, i32, vp, f, C.POINTER(sp_ewma_params),
                                           vp, vp, vp, u32, vp]
     L.swiftprune_score_select.restype = i32
+    L.swiftprune_score_select_group.argtypes = [C.POINTER(sp_matrix), i32, i64, i32, vp, f,
+                                                C.POINTER(sp_ewma_params), u32, vp]
+    L.swiftprune_score_select_group.restype = i32
+    L.swiftprune_nm_select_group.argtypes = [C.POINTER(sp_matrix), i32, i64, i32, vp, i32, i32, u32, vp]
+    L.swiftprune_nm_select_group.restype = i32
     L.swiftprune_nm_select.argtypes = [vp, i64, i64, i64, i32, vp, i32, i32, vp, vp, u32, vp]
     L.swiftprune_nm_select.restype = i32
     L.swiftprune_apply.argtypes = [vp, i64, i64, i64, i32, vp, vp]
@@ -216,6 +229,49 @@ def swiftprune_nm_select(W, hr, n_keep: int, m_group: int, keep_mask, scores=Non
     _check(code, "swiftprune_nm_select")
 
 
+def _group(Ws, keep_masks, row_pruned):
+    """Marshals a list of matrices into an sp_matrix array: (array, n, columns, dtype code)."""
+    import torch
+    n = len(Ws)
+    if not 1 <= n <= SP_MAX_GROUP or len(keep_masks) != n or (row_pruned is not None and len(row_pruned) != n):
+        raise ValueError(f"a group holds 1..{SP_MAX_GROUP} matrices with one mask (and count vector) each")
+    arr = (sp_matrix * n)()
+    n_in, dt = None, None
+    for j, W in enumerate(Ws):
+        ptr, out, cols, ldw, code = _matrix(W)
+        if n_in is None:
+            n_in, dt = cols, code
+        elif (cols, code) != (n_in, dt):
+            raise ValueError("the matrices of a group share the number of columns and the dtype")
+        words = (cols + 31) // 32
+        arr[j] = sp_matrix(ptr, out, ldw, _vec(keep_masks[j], torch.int32, out * words, "keep_mask"),
+                           None if row_pruned is None else _vec(row_pruned[j], torch.int32, out, "row_pruned"))
+    return arr, n, n_in, dt
+
+
+def swiftprune_score_select_group(Ws, hr, keep_masks, sparsity: float = 0.5, alpha: float = 0.125,
+                                  beta: float = 0.125, la: float | None = None, row_pruned=None, flags: int = 0,
+                                  stream=None):
+    """EWMA selection of several matrices that share one layer input (one hr) in one launch."""
+    import torch
+    arr, n, n_in, dt = _group(Ws, keep_masks, row_pruned)
+    params = sp_ewma_params(float(alpha), float(beta), float("nan") if la is None else float(la))
+    code = load_library().swiftprune_score_select_group(
+        arr, n, n_in, dt, _vec(hr, torch.float32, n_in, "hr"), float(sparsity), C.byref(params), int(flags),
+        _stream(stream))
+    _check(code, "swiftprune_score_select_group")
+
+
+def swiftprune_nm_select_group(Ws, hr, n_keep: int, m_group: int, keep_masks, flags: int = 0, stream=None):
+    """N:M selection of several matrices that share one layer input (one hr) in one launch."""
+    import torch
+    arr, n, n_in, dt = _group(Ws, keep_masks, None)
+    code = load_library().swiftprune_nm_select_group(
+        arr, n, n_in, dt, _vec(hr, torch.float32, n_in, "hr"), int(n_keep), int(m_group), int(flags),
+        _stream(stream))
+    _check(code, "swiftprune_nm_select_group")
+
+
 def swiftprune_ewma_trace(W, hr, est=None, dev=None, alpha: float = 0.125, beta: float = 0.125, stream=None):
     """est[out, in], dev[out, in] (fp32 GPU tensors, either may be None) = EWMA state after each weight."""
     import torch
@@ -343,3 +399,20 @@ def prune_layer(W, X, buffers: LayerBuffers | None = None, sparsity: float = 0.5
     else:
         swiftprune_nm_select(W, b.hr, nm[0], nm[1], b.keep_mask, flags=SP_APPLY_INPLACE, stream=stream)
     return b
+
+
+def prune_group(Ws, X, buffers, sparsity: float = 0.5, nm=None, alpha: float = 0.125, beta: float = 0.125,
+                la: float | None = None, stream=None):
+    """Matrices that share the layer input X (q / k / v, gate / up), in place: ONE statistics pass, then one
+    selection + apply launch over all of them.  buffers: one LayerBuffers per matrix; the statistics land
+    in buffers[0] (xsq, S, hr, workspace), masks and counts in each matrix's own."""
+    b0 = buffers[0]
+    swiftprune_layer_stats(X, b0.xsq, b0.S, b0.hr, workspace=b0.workspace, stream=stream)
+    masks = [b.keep_mask for b in buffers]
+    if nm is None:
+        swiftprune_score_select_group(Ws, b0.hr, masks, sparsity=sparsity, alpha=alpha, beta=beta, la=la,
+                                      row_pruned=[b.row_pruned for b in buffers], flags=SP_APPLY_INPLACE,
+                                      stream=stream)
+    else:
+        swiftprune_nm_select_group(Ws, b0.hr, nm[0], nm[1], masks, flags=SP_APPLY_INPLACE, stream=stream)
+    return buffers

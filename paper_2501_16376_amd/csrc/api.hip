@@ -130,6 +130,82 @@ int swiftprune_score_select(const void* W, int64_t out, int64_t in, int64_t ldw,
     return e == hipSuccess ? SP_OK : SP_EHIP;
 }
 
+static bool group_ok(const sp_matrix* mats, int n_mats, int64_t in, int dt) {
+    if (mats == nullptr || n_mats < 1 || n_mats > SP_MAX_GROUP || in <= 0 || !dtype_ok(dt)) return false;
+    for (int j = 0; j < n_mats; ++j) {
+        const sp_matrix& m = mats[j];
+        if (m.W == nullptr || m.keep_mask == nullptr || m.out <= 0 || m.ldw < in) return false;
+        if (reinterpret_cast<uintptr_t>(m.W) % elem_size(dt) != 0) return false;
+    }
+    return true;
+}
+
+static sp::RowGroups make_groups(const sp_matrix* mats, int n_mats) {
+    sp::RowGroups g;
+    g.n = n_mats;
+    int64_t end = 0;
+    for (int j = 0; j < sp::kMaxGroup; ++j) {
+        const sp_matrix& m = mats[j < n_mats ? j : n_mats - 1];
+        if (j < n_mats) end += m.out;
+        g.row_end[j] = end;
+        g.W[j] = m.W;
+        g.ldw[j] = m.ldw;
+        g.keep_mask[j] = m.keep_mask;
+        g.row_pruned[j] = m.row_pruned;
+    }
+    return g;
+}
+
+int swiftprune_score_select_group(const sp_matrix* mats, int n_mats, int64_t in, sp_dtype dt,
+                                  const float* hr, float sparsity, const sp_ewma_params* params,
+                                  uint32_t flags, void* hip_stream) {
+    static_assert(SP_MAX_GROUP == sp::kMaxGroup, "group size of the header and of the kernels");
+    if (hr == nullptr || !group_ok(mats, n_mats, in, (int)dt)) return SP_EINVAL;
+    if (flags & ~(SP_SEQUENTIAL_ORDER | SP_APPLY_INPLACE)) return SP_EINVAL;
+    sp_ewma_params p = {0.125f, 0.125f, NAN};
+    if (params != nullptr) p = *params;
+    if (isnan(p.la) && swiftprune_la_for_sparsity(sparsity, &p.la) != SP_OK) return SP_EINVAL;
+    if (!(p.alpha > 0.0f && p.alpha <= 1.0f) || !(p.beta > 0.0f && p.beta <= 1.0f) || isinf(p.la))
+        return SP_EINVAL;
+    bool fast = !(flags & SP_SEQUENTIAL_ORDER) && p.alpha < 1.0f;
+    for (int j = 0; j < n_mats && fast; ++j) fast = weight_vec_ok(mats[j].W, in, mats[j].ldw, (int)dt, hr, nullptr);
+    if (fast) {
+        const sp::EwmaConsts c = sp::make_ewma_consts(p.alpha, p.beta, p.la);
+        const hipError_t e = sp::launch_ewma_team(make_groups(mats, n_mats), in, (int)dt, hr, c,
+                                                  (flags & SP_APPLY_INPLACE) != 0, 0,
+                                                  static_cast<hipStream_t>(hip_stream));
+        return e == hipSuccess ? SP_OK : SP_EHIP;
+    }
+    for (int j = 0; j < n_mats; ++j) {
+        const int rc = swiftprune_score_select(mats[j].W, mats[j].out, in, mats[j].ldw, dt, hr, sparsity, &p,
+                                               mats[j].keep_mask, mats[j].row_pruned, nullptr, flags, hip_stream);
+        if (rc != SP_OK) return rc;
+    }
+    return SP_OK;
+}
+
+int swiftprune_nm_select_group(const sp_matrix* mats, int n_mats, int64_t in, sp_dtype dt, const float* hr,
+                               int n_keep, int m_group, uint32_t flags, void* hip_stream) {
+    if (hr == nullptr || !group_ok(mats, n_mats, in, (int)dt)) return SP_EINVAL;
+    if (m_group != 4 && m_group != 8 && m_group != 16) return SP_EINVAL;
+    if (n_keep <= 0 || n_keep >= m_group || in % m_group != 0) return SP_EINVAL;
+    if (flags & ~SP_APPLY_INPLACE) return SP_EINVAL;
+    bool fast = true;
+    for (int j = 0; j < n_mats && fast; ++j) fast = weight_vec_ok(mats[j].W, in, mats[j].ldw, (int)dt, hr, nullptr);
+    if (fast) {
+        const hipError_t e = sp::launch_nm_select_group(make_groups(mats, n_mats), in, (int)dt, hr, n_keep, m_group,
+                                                        nullptr, (flags & SP_APPLY_INPLACE) != 0,
+                                                        static_cast<hipStream_t>(hip_stream));
+        return e == hipSuccess ? SP_OK : SP_EHIP;
+    }
+    for (int j = 0; j < n_mats; ++j) {
+        const int rc = swiftprune_nm_select(mats[j].W, mats[j].out, in, mats[j].ldw, dt, hr, n_keep, m_group,
+                                            mats[j].keep_mask, nullptr, flags, hip_stream);
+        if (rc != SP_OK) return rc;
+    }
+    return SP_OK;
+}
+
 int swiftprune_ewma_trace(const void* W, int64_t out, int64_t in, int64_t ldw, sp_dtype dt,
                           const float* hr, float alpha, float beta, float* est, float* dev,
                           void* hip_stream) {

@@ -221,6 +221,27 @@ __device__ __forceinline__ float score_of(float w, float factor) {
     return __fmul_rn(w2, factor);
 }
 
+// Which matrix of a group a consecutively numbered row belongs to, and its row number inside that matrix.
+// Wave-uniform input gives wave-uniform results (scalar selects).
+template <class Groups>
+struct RowOwner {
+    void* W;
+    int64_t ldw, row;
+    uint32_t* keep_mask;
+    int32_t* row_pruned;
+    __device__ __forceinline__ RowOwner(const Groups& g, int64_t global_row) {
+        W = g.W[0]; ldw = g.ldw[0]; keep_mask = g.keep_mask[0]; row_pruned = g.row_pruned[0];
+        row = global_row;
+#pragma unroll
+        for (int j = 1; j < (int)(sizeof(g.row_end) / sizeof(g.row_end[0])); ++j) {
+            if (j < g.n && global_row >= g.row_end[j - 1]) {
+                W = g.W[j]; ldw = g.ldw[j]; keep_mask = g.keep_mask[j]; row_pruned = g.row_pruned[j];
+                row = global_row - g.row_end[j - 1];
+            }
+        }
+    }
+};
+
 __device__ __forceinline__ void store8(float* dst, const float* v, bool vec, int valid) {
     if (vec) {
         reinterpret_cast<float4*>(dst)[0] = make_float4(v[0], v[1], v[2], v[3]);

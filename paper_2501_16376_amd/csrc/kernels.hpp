@@ -29,6 +29,19 @@ hipError_t launch_layer_stats(const void* X, int64_t tokens, int64_t in, int64_t
                               float* xsq, float* S, float* hr, int accumulate, int finalize,
                               void* workspace, hipStream_t stream);
 
+// ---- several weight matrices that share one layer input (same columns, same channel factor), pruned by
+// one launch: the rows of all matrices are numbered consecutively, matrix j owning [row_end[j-1], row_end[j]) ----
+constexpr int kMaxGroup = 8;
+struct RowGroups {
+    int n;                          // matrices in use (1 .. kMaxGroup)
+    int64_t row_end[kMaxGroup];     // running totals of the row counts; unused entries repeat the last total
+    void* W[kMaxGroup];
+    int64_t ldw[kMaxGroup];
+    uint32_t* keep_mask[kMaxGroup];
+    int32_t* row_pruned[kMaxGroup];  // nullable per matrix
+    __host__ __device__ int64_t total() const { return row_end[kMaxGroup - 1]; }
+};
+
 // ---- steps 2+3: EWMA selection ----
 struct EwmaConsts {
     float alpha, beta, la;
@@ -45,9 +58,9 @@ hipError_t launch_ewma_scan(const void* W, int64_t out, int64_t in, int64_t ldw,
                             const float* hr, const EwmaConsts& c, uint32_t* keep_mask,
                             int32_t* row_pruned, float* scores, bool apply, hipStream_t stream);
 // fast path for the 16-byte-vector layout and alpha < 1; team = wavefronts per row (1, 2, 4; 0 = by row count)
-hipError_t launch_ewma_team(const void* W, int64_t out, int64_t in, int64_t ldw, int dt, const float* hr,
-                            const EwmaConsts& c, uint32_t* keep_mask, int32_t* row_pruned, bool apply,
-                            int team, hipStream_t stream);
+hipError_t launch_ewma_team(const RowGroups& g, int64_t in, int dt, const float* hr, const EwmaConsts& c,
+                            bool apply, int team, hipStream_t stream);
+RowGroups single_matrix(const void* W, int64_t out, int64_t ldw, uint32_t* keep_mask, int32_t* row_pruned);
 hipError_t launch_ewma_sequential(const void* W, int64_t out, int64_t in, int64_t ldw, int dt,
                                   const float* hr, float alpha, float beta, float la,
                                   uint32_t* keep_mask, int32_t* row_pruned, float* scores, bool apply,
@@ -86,6 +99,9 @@ hipError_t launch_expand_nm(const void* values, const uint32_t* meta, int64_t ou
 hipError_t launch_nm_select(const void* W, int64_t out, int64_t in, int64_t ldw, int dt, bool vec,
                             const float* hr, int n_keep, int m_group, uint32_t* keep_mask,
                             float* scores, bool apply, hipStream_t stream);
+// N:M selection of a group of matrices in one launch (16-byte-vector layout only)
+hipError_t launch_nm_select_group(const RowGroups& g, int64_t in, int dt, const float* hr, int n_keep,
+                                  int m_group, float* scores, bool apply, hipStream_t stream);
 hipError_t launch_apply(void* W, int64_t out, int64_t in, int64_t ldw, int dt, bool vec,
                         const uint32_t* keep_mask, hipStream_t stream);
 

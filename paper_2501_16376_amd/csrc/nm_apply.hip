@@ -195,15 +195,15 @@ BandPlan make_band_plan(int64_t out, int64_t in, int target_groups, int unroll =
 
 template <int DT, int M, int U>
 __global__ __launch_bounds__(kColThreads) void nm_select_band_kernel(
-    void* __restrict__ W, int64_t out, int64_t in, int64_t ldw, const float* __restrict__ hr,
-    int n_prune, uint32_t* __restrict__ keep_mask, float* __restrict__ scores, int apply,
-    int strip_units) {
+    const RowGroups g, int64_t in, const float* __restrict__ hr, int n_prune, float* __restrict__ scores,
+    int apply, int strip_units) {
     const int lane = threadIdx.x & (kWave - 1);
     const int64_t unit = (int64_t)blockIdx.x * strip_units + threadIdx.x;
     const int64_t q0 = unit * 8;
     const bool active = (int)threadIdx.x < strip_units && q0 < in;  // in % 8 == 0 on this path
     const int64_t mask_words = (in + 31) >> 5;
     const int64_t step = (int64_t)gridDim.y * U;
+    const int64_t out = g.total();  // rows of all matrices of the group, numbered consecutively
 
     Factor8 f;
     if (active) f.load_vec(hr, q0); else f.load_elems(hr, 0, 0);
@@ -211,25 +211,30 @@ __global__ __launch_bounds__(kColThreads) void nm_select_band_kernel(
     auto fetch = [&](Chunk8<DT>* w, int64_t r0) {
 #pragma unroll
         for (int j = 0; j < U; ++j) {
-            if (active && r0 + j < out) w[j].load_vec(W, (r0 + j) * ldw + q0); else w[j].zero();
+            if (active && r0 + j < out) {
+                const RowOwner<RowGroups> own(g, r0 + j);
+                w[j].load_vec(own.W, own.row * own.ldw + q0);
+            } else {
+                w[j].zero();
+            }
         }
     };
     auto work = [&](Chunk8<DT>* w, int64_t r0) {
 #pragma unroll
         for (int j = 0; j < U; ++j) {
-            const int64_t row = r0 + j;
-            if (row >= out) break;  // uniform over the workgroup
+            if (r0 + j >= out) break;  // uniform over the workgroup
+            const RowOwner<RowGroups> own(g, r0 + j);
             float L[8];
 #pragma unroll
             for (int k = 0; k < 8; ++k) L[k] = score_of(w[j].get(k), f.v[k]);
             uint32_t keep = (M == 16) ? nm_keep_bits16(L, n_prune, lane) : nm_keep_bits<(M == 16 ? 8 : M)>(L, n_prune);
             if (!active) keep = 0u;
-            if (scores != nullptr && active) store8(scores + row * in + q0, L, true, 8);
+            if (scores != nullptr && active) store8(scores + (r0 + j) * in + q0, L, true, 8);  // single matrix only
             const uint32_t word = quad_gather_bytes(keep, lane);
-            if ((lane & 3) == 0 && active) keep_mask[row * mask_words + (q0 >> 5)] = word;
+            if ((lane & 3) == 0 && active) own.keep_mask[own.row * mask_words + (q0 >> 5)] = word;
             if (apply && active) {
                 w[j].apply(keep);
-                w[j].store_vec_nt(W, row * ldw + q0);
+                w[j].store_vec_nt(own.W, own.row * own.ldw + q0);
             }
         }
     };
@@ -300,16 +305,15 @@ constexpr int kApplyBandGroups = 512;
 constexpr int kSelectBandGroups = 768;
 
 template <int DT, int M>
-static hipError_t launch_nm_band(void* W, int64_t out, int64_t in, int64_t ldw, const float* hr, int n_prune,
-                                 uint32_t* keep_mask, float* scores, int apply, int target_groups,
-                                 hipStream_t stream, int unroll = 4) {
-    const BandPlan p = make_band_plan(out, in, target_groups, unroll);
+static hipError_t launch_nm_band(const RowGroups& g, int64_t in, const float* hr, int n_prune, float* scores,
+                                 int apply, int target_groups, hipStream_t stream, int unroll = 4) {
+    const BandPlan p = make_band_plan(g.total(), in, target_groups, unroll);
     const dim3 grid((unsigned)p.nstrips, (unsigned)p.splits), block(kColThreads);
     switch (p.unroll) {
-        case 8: hipLaunchKernelGGL((nm_select_band_kernel<DT, M, 8>), grid, block, 0, stream, W, out, in, ldw, hr, n_prune, keep_mask, scores, apply, p.strip_units); break;
-        case 4: hipLaunchKernelGGL((nm_select_band_kernel<DT, M, 4>), grid, block, 0, stream, W, out, in, ldw, hr, n_prune, keep_mask, scores, apply, p.strip_units); break;
-        case 2: hipLaunchKernelGGL((nm_select_band_kernel<DT, M, 2>), grid, block, 0, stream, W, out, in, ldw, hr, n_prune, keep_mask, scores, apply, p.strip_units); break;
-        default: hipLaunchKernelGGL((nm_select_band_kernel<DT, M, 1>), grid, block, 0, stream, W, out, in, ldw, hr, n_prune, keep_mask, scores, apply, p.strip_units); break;
+        case 8: hipLaunchKernelGGL((nm_select_band_kernel<DT, M, 8>), grid, block, 0, stream, g, in, hr, n_prune, scores, apply, p.strip_units); break;
+        case 4: hipLaunchKernelGGL((nm_select_band_kernel<DT, M, 4>), grid, block, 0, stream, g, in, hr, n_prune, scores, apply, p.strip_units); break;
+        case 2: hipLaunchKernelGGL((nm_select_band_kernel<DT, M, 2>), grid, block, 0, stream, g, in, hr, n_prune, scores, apply, p.strip_units); break;
+        default: hipLaunchKernelGGL((nm_select_band_kernel<DT, M, 1>), grid, block, 0, stream, g, in, hr, n_prune, scores, apply, p.strip_units); break;
     }
     return hipGetLastError();
 }
@@ -365,17 +369,24 @@ hipError_t launch_nm_select(const void* W, int64_t out, int64_t in, int64_t ldw,
                             float* scores, bool apply, hipStream_t stream) {
     return with_dtype(dt, [&](auto tag) {
         constexpr int DT = decltype(tag)::value;
-        if (vec) {
-            void* Wm = const_cast<void*>(W);
-            const int n_prune = m_group - n_keep, ap = apply ? 1 : 0;
-            switch (m_group) {
-                case 4: return launch_nm_band<DT, 4>(Wm, out, in, ldw, hr, n_prune, keep_mask, scores, ap, kSelectBandGroups, stream);
-                case 8: return launch_nm_band<DT, 8>(Wm, out, in, ldw, hr, n_prune, keep_mask, scores, ap, kSelectBandGroups, stream);
-                case 16: return launch_nm_band<DT, 16>(Wm, out, in, ldw, hr, n_prune, keep_mask, scores, ap, kSelectBandGroups, stream);
-                default: return hipErrorInvalidValue;
-            }
-        }
+        if (vec)
+            return launch_nm_select_group(single_matrix(W, out, ldw, keep_mask, nullptr), in, DT, hr, n_keep, m_group,
+                                          scores, apply, stream);
         return launch_nm_t<DT, false>(W, out, in, ldw, hr, n_keep, m_group, keep_mask, scores, apply, stream);
+    });
+}
+
+hipError_t launch_nm_select_group(const RowGroups& g, int64_t in, int dt, const float* hr, int n_keep,
+                                  int m_group, float* scores, bool apply, hipStream_t stream) {
+    const int n_prune = m_group - n_keep, ap = apply ? 1 : 0;
+    return with_dtype(dt, [&](auto tag) {
+        constexpr int DT = decltype(tag)::value;
+        switch (m_group) {
+            case 4: return launch_nm_band<DT, 4>(g, in, hr, n_prune, scores, ap, kSelectBandGroups, stream);
+            case 8: return launch_nm_band<DT, 8>(g, in, hr, n_prune, scores, ap, kSelectBandGroups, stream);
+            case 16: return launch_nm_band<DT, 16>(g, in, hr, n_prune, scores, ap, kSelectBandGroups, stream);
+            default: return hipErrorInvalidValue;
+        }
     });
 }
 

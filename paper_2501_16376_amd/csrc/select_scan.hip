@@ -101,7 +101,7 @@ hipError_t launch_ewma_scan(const void* W, int64_t out, int64_t in, int64_t ldw,
     return with_dtype(dt, [&](auto tag) {
         constexpr int DT = decltype(tag)::value;
         if (vec && scores == nullptr && c.alpha < 1.0f)   // the fast path (select_team.hip)
-            return launch_ewma_team(W, out, in, ldw, DT, hr, c, keep_mask, row_pruned, apply, 0, stream);
+            return launch_ewma_team(single_matrix(W, out, ldw, keep_mask, row_pruned), in, DT, hr, c, apply, 0, stream);
         return vec ? launch_scan_t<DT, true>(W, out, in, ldw, hr, c, keep_mask, row_pruned, scores, apply, stream)
                    : launch_scan_t<DT, false>(W, out, in, ldw, hr, c, keep_mask, row_pruned, scores, apply, stream);
     });

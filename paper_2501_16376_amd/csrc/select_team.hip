@@ -133,12 +133,11 @@ struct Unpacked8 {
     }
 };
 
-// grid = ceil(out / (4 / NW)), block = 256 (4 wavefronts).  Requires the 16-byte-vector layout
+// grid = ceil(rows of all matrices / (4 / NW)), block = 256 (4 wavefronts).  Requires the 16-byte-vector layout
 // (W and hr 16-byte aligned, in % 8 == 0, ldw a multiple of 16 bytes) and alpha < 1.
 template <int DT, int NW>
 __global__ __launch_bounds__(kTeamThreads) void ewma_team_kernel(
-    void* __restrict__ W, int64_t out, int64_t in, int64_t ldw, const float* __restrict__ hr,
-    const EwmaConsts c, uint32_t* __restrict__ keep_mask, int32_t* __restrict__ row_pruned, int apply) {
+    const RowGroups g, int64_t in, const float* __restrict__ hr, const EwmaConsts c, int apply) {
     constexpr int kRowsPerGroup = 4 / NW;
     __shared__ float lds_x[kRowsPerGroup][NW];
     __shared__ float lds_y[kRowsPerGroup][NW];
@@ -146,14 +145,20 @@ __global__ __launch_bounds__(kTeamThreads) void ewma_team_kernel(
     __shared__ int lds_count[kRowsPerGroup][NW];
 
     const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // uniform: the row lookup below stays scalar
     const int slot = wave / NW;  // which row of the workgroup
     const int part = wave % NW;  // which run of the row's spans
-    const int64_t row = (int64_t)blockIdx.x * kRowsPerGroup + slot;
+    const int64_t global_row = (int64_t)blockIdx.x * kRowsPerGroup + slot;
+    const bool has_row = global_row < g.total();
     // a wavefront without a row (past the last one) still walks the loop and meets the barriers, with all
     // its lanes switched off
-    const int64_t cols = row < out ? in : 0;
-    const int64_t row_off = row * ldw;
+    const RowOwner<RowGroups> own(g, has_row ? global_row : 0);
+    void* const W = own.W;
+    uint32_t* const keep_mask = own.keep_mask;
+    int32_t* const row_pruned = own.row_pruned;
+    const int64_t row = own.row;
+    const int64_t cols = has_row ? in : 0;
+    const int64_t row_off = row * own.ldw;
     const int64_t mask_words = (in + 31) >> 5;
     const int64_t span_cols = (int64_t)NW * kSegs * 512;
     const int64_t nspans = (in + span_cols - 1) / span_cols;
@@ -183,7 +188,7 @@ __global__ __launch_bounds__(kTeamThreads) void ewma_team_kernel(
     int pruned = 0;
     // lanes past the end of the row (and wavefronts without a row) read valid memory and compute on it, but
     // store nothing: whatever they compute can only reach columns to their right, which do not exist either
-    const int64_t row_off_ld = (row < out ? row : 0) * ldw;
+    const int64_t row_off_ld = row_off;
 
     for (int64_t span = 0; span < nspans; ++span) {
         const int64_t q_run = span * span_cols + (int64_t)part * (kSegs * 512) + (int64_t)lane * 8;
@@ -298,49 +303,61 @@ __global__ __launch_bounds__(kTeamThreads) void ewma_team_kernel(
         }
     }
 
-    if (row_pruned != nullptr) {
+    // counts: unconditional, so that every wavefront of the workgroup meets the barrier
+    {
 #pragma unroll
         for (int off = 32; off > 0; off >>= 1) pruned += __shfl_xor(pruned, off, kWave);
         if (NW > 1) {
             if (lane == 0) lds_count[slot][part] = pruned;
             team_barrier();
-            if (lane == 0 && part == 0 && row < out) {
+            if (lane == 0 && part == 0 && has_row && row_pruned != nullptr) {
                 int total = 0;
 #pragma unroll
                 for (int v = 0; v < NW; ++v) total += lds_count[slot][v];
                 row_pruned[row] = total;
             }
-        } else if (lane == 0 && row < out) {
+        } else if (lane == 0 && has_row && row_pruned != nullptr) {
             row_pruned[row] = pruned;
         }
     }
 }
 
 template <int DT, int NW>
-static hipError_t launch_team_t(void* W, int64_t out, int64_t in, int64_t ldw, const float* hr,
-                                const EwmaConsts& c, uint32_t* keep_mask, int32_t* row_pruned, bool apply,
+static hipError_t launch_team_t(const RowGroups& g, int64_t in, const float* hr, const EwmaConsts& c, bool apply,
                                 hipStream_t stream) {
     constexpr int rows = 4 / NW;
-    const int64_t groups = (out + rows - 1) / rows;
+    const int64_t groups = (g.total() + rows - 1) / rows;
     if (groups > 0x7fffffff) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((ewma_team_kernel<DT, NW>), dim3((unsigned)groups), dim3(kTeamThreads), 0, stream, W, out, in,
-                       ldw, hr, c, keep_mask, row_pruned, apply ? 1 : 0);
+    hipLaunchKernelGGL((ewma_team_kernel<DT, NW>), dim3((unsigned)groups), dim3(kTeamThreads), 0, stream, g, in, hr, c,
+                       apply ? 1 : 0);
     return hipGetLastError();
 }
 
+RowGroups single_matrix(const void* W, int64_t out, int64_t ldw, uint32_t* keep_mask, int32_t* row_pruned) {
+    RowGroups g;
+    g.n = 1;
+    for (int j = 0; j < kMaxGroup; ++j) {
+        g.row_end[j] = out;
+        g.W[j] = const_cast<void*>(W);
+        g.ldw[j] = ldw;
+        g.keep_mask[j] = keep_mask;
+        g.row_pruned[j] = row_pruned;
+    }
+    return g;
+}
+
 // team size: `team` = 1, 2 or 4 wavefronts per row; 0 picks by the number of rows
-hipError_t launch_ewma_team(const void* W, int64_t out, int64_t in, int64_t ldw, int dt, const float* hr,
-                            const EwmaConsts& c, uint32_t* keep_mask, int32_t* row_pruned, bool apply,
-                            int team, hipStream_t stream) {
+hipError_t launch_ewma_team(const RowGroups& g, int64_t in, int dt, const float* hr, const EwmaConsts& c,
+                            bool apply, int team, hipStream_t stream) {
     // at least four wavefronts per SIMD (1024 SIMDs) before a row gets a wavefront to itself
+    const int64_t out = g.total();
     if (team == 0) team = out <= 1024 ? 4 : (out <= 2048 ? 2 : 1);
-    void* Wm = const_cast<void*>(W);
     return with_dtype(dt, [&](auto tag) {
         constexpr int DT = decltype(tag)::value;
         switch (team) {
-            case 4: return launch_team_t<DT, 4>(Wm, out, in, ldw, hr, c, keep_mask, row_pruned, apply, stream);
-            case 2: return launch_team_t<DT, 2>(Wm, out, in, ldw, hr, c, keep_mask, row_pruned, apply, stream);
-            default: return launch_team_t<DT, 1>(Wm, out, in, ldw, hr, c, keep_mask, row_pruned, apply, stream);
+            case 4: return launch_team_t<DT, 4>(g, in, hr, c, apply, stream);
+            case 2: return launch_team_t<DT, 2>(g, in, hr, c, apply, stream);
+            default: return launch_team_t<DT, 1>(g, in, hr, c, apply, stream);
         }
     });
 }

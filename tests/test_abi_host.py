@@ -129,6 +129,24 @@ def test_argument_checks_do_not_launch(lib):
     assert nm(p, 8, 8, 8, 1, p, 0, 4, p, None, 0, None) == E
     assert nm(p, 8, 12, 12, 1, p, 4, 8, p, None, 0, None) == E        # in % m != 0
     assert nm(p, 8, 8, 8, 1, p, 2, 4, p, None, 1, None) == E          # strict-order flag not valid here
+    grp, ngrp = lib.swiftprune_score_select_group, lib.swiftprune_nm_select_group
+    ok = binding.sp_matrix(p, 8, 8, p, None)
+    two = (binding.sp_matrix * 2)(ok, ok)
+    assert grp(None, 1, 8, 1, p, 0.5, C.byref(prm), 0, None) == E
+    assert grp(two, 0, 8, 1, p, 0.5, C.byref(prm), 0, None) == E
+    assert grp(two, 9, 8, 1, p, 0.5, C.byref(prm), 0, None) == E             # more than SP_MAX_GROUP
+    assert grp(two, 2, 8, 1, None, 0.5, C.byref(prm), 0, None) == E
+    assert grp(two, 2, 8, 1, p, 0.5, C.byref(prm), 64, None) == E
+    assert grp(two, 2, 8, 1, p, 0.3, C.byref(nanla), 0, None) == E
+    for broken in (binding.sp_matrix(None, 8, 8, p, None), binding.sp_matrix(p, 0, 8, p, None),
+                   binding.sp_matrix(p, 8, 7, p, None), binding.sp_matrix(p, 8, 8, None, None),
+                   binding.sp_matrix(p + 1, 8, 8, p, None)):
+        arr = (binding.sp_matrix * 2)(ok, broken)
+        assert grp(arr, 2, 8, 1, p, 0.5, C.byref(prm), 0, None) == E
+        assert ngrp(arr, 2, 8, 1, p, 2, 4, 0, None) == E
+    assert ngrp(two, 2, 8, 1, p, 2, 5, 0, None) == E
+    assert ngrp(two, 2, 12, 1, p, 4, 8, 0, None) == E                        # in % m != 0 (and pitch < columns)
+    assert ngrp(two, 2, 8, 1, p, 2, 4, 1, None) == E
     cf = lib.swiftprune_channel_factor
     assert cf(None, p, 8, p, None) == E and cf(p, None, 8, p, None) == E and cf(p, p, 8, None, None) == E
     assert cf(p, p, 0, p, None) == E and cf(p + 2, p, 8, p, None) == E

@@ -309,3 +309,87 @@ def test_channel_factor_and_sharded_tokens(orc, gpu):
     assert np.allclose(xsq_sum.cpu().numpy(), xsq_o, rtol=1e-5, atol=0)
     assert abs(float(S_sum.item()) - S_o) <= 1e-5 * S_o
     assert np.allclose(hr.cpu().numpy(), hr_o, rtol=1e-5, atol=0)
+
+
+@pytest.mark.parametrize("outs,n,dtype,pad", [
+    ((96, 24, 24), 1024, "bf16", 0),          # q / k / v-like: one long, two short matrices
+    ((300, 1100, 7), 2056, "bf16", 0),        # more than 1024 rows in all: other team sizes than the singles
+    ((40, 40), 1000, "f16", 24),              # padded pitch
+    ((33, 5), 1001, "bf16", 0),               # odd width: not the fast layout, one launch per matrix
+    ((64, 64, 64, 64, 64, 64, 64, 64), 520, "f32", 0),   # a full group of eight, fp32
+])
+def test_group_selection_matches_per_matrix_oracle(orc, gpu, outs, n, dtype, pad):
+    """Matrices sharing one layer input, pruned by ONE statistics pass and one grouped selection launch:
+    every matrix against the oracle run on it alone (EWMA under the threshold rule, counts, fused apply;
+    N:M bit-exact), beside the single-matrix entry points held to the same bar (the two may stitch a row
+    from different numbers of pieces, so their est/dev can differ in the last bits)."""
+    import torch
+    from paper_2501_16376_amd import binding as b, synth
+    from gpu_util import to_device, check_ewma_mask, mask_to_host, same_bits
+    say(f"[case] group outs={outs} in={n} {dtype} pad={pad}")
+    tokens = 300
+    _, Xh = synth.layer_inputs(1, n, tokens, seed=n, dtype=dtype)
+    Whs = [synth.layer_inputs(o, n, 1, seed=1000 + 7 * j + o, dtype=dtype)[0] for j, o in enumerate(outs)]
+    xsq_o, S_o, hr_o = orc.layer_stats(Xh)
+    X = to_device(Xh, gpu)
+
+    def fresh():
+        Ws = []
+        for Wh in Whs:
+            if pad:
+                Wp = np.zeros((Wh.shape[0], n + pad), dtype=Wh.dtype)
+                Wp[:, :n] = Wh
+                Ws.append(to_device(Wp, gpu)[:, :n])
+            else:
+                Ws.append(to_device(Wh, gpu))
+        return Ws
+
+    bufs = [b.LayerBuffers(o, n, tokens, gpu) for o in outs]
+    for bb in bufs:
+        bb.keep_mask.fill_(-1)
+        bb.row_pruned.fill_(-7)
+    # ---- the whole grouped path on the GPU's own statistics
+    Ws = fresh()
+    b.prune_group(Ws, X, bufs, la=0.5)
+    torch.cuda.synchronize()
+    assert np.allclose(bufs[0].hr.cpu().numpy(), hr_o, rtol=1e-5, atol=0)
+    for Wh, W, bb in zip(Whs, Ws, bufs):
+        m = mask_to_host(bb.keep_mask)
+        check_ewma_mask(orc, Wh, hr_o, A, B, 0.5, m, bb.row_pruned.cpu().numpy())
+        assert same_bits(synth.torch_to_host_bits(W), orc.apply(Wh.copy(), m))
+    # ---- same factor as the oracle: grouped and single-matrix calls
+    hr_dev = to_device(hr_o, gpu)
+    Ws, Ws1 = fresh(), fresh()
+    masks = [torch.full_like(bb.keep_mask, -1) for bb in bufs]
+    cnts = [torch.full_like(bb.row_pruned, -7) for bb in bufs]
+    b.swiftprune_score_select_group(Ws, hr_dev, masks, la=-0.2, row_pruned=cnts, flags=b.SP_APPLY_INPLACE)
+    for W1, bb in zip(Ws1, bufs):
+        b.swiftprune_score_select(W1, hr_dev, bb.keep_mask, la=-0.2, row_pruned=bb.row_pruned, flags=b.SP_APPLY_INPLACE)
+    torch.cuda.synchronize()
+    for Wh, W, W1, m, c, bb in zip(Whs, Ws, Ws1, masks, cnts, bufs):
+        check_ewma_mask(orc, Wh, hr_o, A, B, -0.2, mask_to_host(m), c.cpu().numpy())
+        check_ewma_mask(orc, Wh, hr_o, A, B, -0.2, mask_to_host(bb.keep_mask), bb.row_pruned.cpu().numpy())
+        assert same_bits(synth.torch_to_host_bits(W), orc.apply(Wh.copy(), mask_to_host(m)))
+        assert same_bits(synth.torch_to_host_bits(W1), orc.apply(Wh.copy(), mask_to_host(bb.keep_mask)))
+    # the strict-order flag goes matrix by matrix and is bit-exact with the oracle
+    b.swiftprune_score_select_group(fresh(), hr_dev, masks, la=0.5, row_pruned=cnts, flags=b.SP_SEQUENTIAL_ORDER)
+    torch.cuda.synchronize()
+    for Wh, m, c in zip(Whs, masks, cnts):
+        mo, co, _ = orc.ewma_select(Wh, hr_o, A, B, 0.5)
+        assert np.array_equal(mask_to_host(m), mo) and np.array_equal(c.cpu().numpy(), co)
+    # ---- N:M
+    for nk, mg in ((2, 4), (4, 8)):
+        if n % mg:
+            continue
+        Ws = fresh()
+        for m in masks:
+            m.fill_(-1)
+        b.swiftprune_nm_select_group(Ws, hr_dev, nk, mg, masks, flags=b.SP_APPLY_INPLACE)
+        torch.cuda.synchronize()
+        for Wh, W, m in zip(Whs, Ws, masks):
+            mo, _ = orc.nm_select(Wh, hr_o, nk, mg)
+            assert np.array_equal(mask_to_host(m), mo), (nk, mg)
+            assert same_bits(synth.torch_to_host_bits(W), orc.apply(Wh.copy(), mo))
+    if pad:
+        for W in Ws:
+            assert np.all(synth.torch_to_host_bits(W._base)[:, n:] == 0)
