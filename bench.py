@@ -365,9 +365,12 @@ def sample_70b(sp, synth, torch, dev, stream, T, storage, blocks, steps):
     W0 = st.pristine[0]
     b0 = st.bufs[0]
     sp.swiftprune_layer_stats(st.X["attn_in"], b0.xsq, b0.S, b0.hr, workspace=b0.workspace, stream=stream)
-    la30, ach30, ok30 = sp.swiftprune_calibrate_la(W0, b0.hr, 0.30, tolerance=1e-3, stream=stream)
+    la_dev = torch.empty(1, dtype=torch.float32, device=dev)
+    status_dev = torch.empty(1, dtype=torch.int32, device=dev)
+    sp.swiftprune_calibrate_la_device(W0, b0.hr, 0.30, la_dev, status_out=status_dev, stream=stream)
+    la30, ok30 = float(la_dev.item()), int(status_dev.item()) == 0      # read back once, for the report
     label = f"llama2-70b-shaped sample, {blocks} of {n_model} blocks x 7 linear layers"
-    for tag, kw in ((f"unstructured, la calibrated for 30 % on one matrix ({'reached' if ok30 else 'closest'})",
+    for tag, kw in ((f"unstructured, la calibrated on the device for 30 % on one matrix ({'exact rank' if ok30 else 'clamped'})",
                      {"la": la30}),
                     ("unstructured, la=0.5 (table: 50 %)", {"la": 0.5}),
                     ("unstructured, la=-0.2 (table: 70 %)", {"la": -0.2}),

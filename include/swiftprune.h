@@ -209,6 +209,37 @@ int swiftprune_calibrate_la(const void *W, int64_t out, int64_t in, int64_t ldw,
                             float *la, float *achieved, void *hip_stream);
 
 /*
+ * The same tuning without the host in the loop (Sec. 3.1 leaves la for ratios outside its table to tuning;
+ * the appendix reports 10-40 % without their la).  With S fixed every weight has a critical multiplier
+ *     lambda = (est_before - L) / dev_before     (+inf / -inf when dev_before == 0),
+ * it is pruned exactly when la < lambda, so the la that prunes k weights is the (k+1)-th largest lambda:
+ * a three-pass radix select over W, entirely on hip_stream, no synchronisation, no copy to the host.
+ *
+ *   target_sparsity  in (0, 1): k = round(target_sparsity * out * in)
+ *   workspace        device scratch, >= swiftprune_la_workspace_bytes(), 256-byte aligned
+ *   la_device        [1] fp32 (device, write): the multiplier; pass it to swiftprune_score_select_la
+ *   pruned_device    nullable [1] uint64 (device, write): weights with lambda > la (= k unless lambdas tie)
+ *   status_device    nullable [1] int32 (device, write): 0, or 1 when rank k falls among weights that are
+ *                    pruned for every la or for none (la is then +-3e38)
+ * est/dev are the scan evaluation of swiftprune_score_select's default path; the pruned count that call
+ * then produces can differ from k by the few weights whose score lies within rounding of its threshold.
+ */
+size_t swiftprune_la_workspace_bytes(void);
+int swiftprune_calibrate_la_device(const void *W, int64_t out, int64_t in, int64_t ldw, sp_dtype dt,
+                                   const float *hr, float alpha, float beta, float target_sparsity,
+                                   void *workspace, size_t workspace_bytes, float *la_device,
+                                   unsigned long long *pruned_device, int *status_device, void *hip_stream);
+
+/*
+ * swiftprune_score_select (default path) with la taken from device memory when the kernel runs, so that a
+ * multiplier calibrated on the same stream is used without a round trip to the host.
+ * flags: SP_APPLY_INPLACE.  Other arguments as for swiftprune_score_select.
+ */
+int swiftprune_score_select_la(const void *W, int64_t out, int64_t in, int64_t ldw, sp_dtype dt,
+                               const float *hr, float alpha, float beta, const float *la_device,
+                               uint32_t *keep_mask, int32_t *row_pruned, uint32_t flags, void *hip_stream);
+
+/*
  * Exact comparator (Sec. 3.1: order a row's scores and drop the lowest ones - the O(n log n) rule
  * the EWMA walk replaces).  In every row the k smallest scores are
  * pruned, equal scores in index order; k = k_per_row[r] when k_per_row != NULL (device, int32[out]),

@@ -19,7 +19,7 @@ SP_OK, SP_EINVAL, SP_ENOSPC, SP_EHIP, SP_ERANGE = 0, -1, -2, -3, -4
 SP_SEQUENTIAL_ORDER, SP_APPLY_INPLACE = 1, 2
 
 EXPORTS = ("swiftprune_layer_stats", "swiftprune_layer_stats_static", "swiftprune_score_select", "swiftprune_nm_select",
-           "swiftprune_apply", "swiftprune_score_select_group", "swiftprune_nm_select_group", "swiftprune_channel_factor", "swiftprune_ewma_trace", "swiftprune_count_pruned", "swiftprune_calibrate_la", "swiftprune_topk_select", "swiftprune_compact_nm", "swiftprune_expand_nm", "swiftprune_nm_meta_words", "swiftprune_la_for_sparsity", "swiftprune_stats_workspace_bytes",
+           "swiftprune_apply", "swiftprune_score_select_group", "swiftprune_nm_select_group", "swiftprune_channel_factor", "swiftprune_ewma_trace", "swiftprune_count_pruned", "swiftprune_calibrate_la", "swiftprune_calibrate_la_device", "swiftprune_la_workspace_bytes", "swiftprune_score_select_la", "swiftprune_topk_select", "swiftprune_compact_nm", "swiftprune_expand_nm", "swiftprune_nm_meta_words", "swiftprune_la_for_sparsity", "swiftprune_stats_workspace_bytes",
            "swiftprune_strerror", "swiftprune_version")
 
 
@@ -80,6 +80,12 @@ def load_library(path: str | None = None) -> C.CDLL:
     L.swiftprune_calibrate_la.argtypes = [vp, i64, i64, i64, i32, vp, f, f, f, f, f, f, vp,
                                           C.POINTER(C.c_float), C.POINTER(C.c_float), vp]
     L.swiftprune_calibrate_la.restype = i32
+    L.swiftprune_la_workspace_bytes.argtypes = []
+    L.swiftprune_la_workspace_bytes.restype = C.c_size_t
+    L.swiftprune_calibrate_la_device.argtypes = [vp, i64, i64, i64, i32, vp, f, f, f, vp, C.c_size_t, vp, vp, vp, vp]
+    L.swiftprune_calibrate_la_device.restype = i32
+    L.swiftprune_score_select_la.argtypes = [vp, i64, i64, i64, i32, vp, f, f, vp, vp, vp, u32, vp]
+    L.swiftprune_score_select_la.restype = i32
     L.swiftprune_topk_select.argtypes = [vp, i64, i64, i64, i32, vp, vp, i64, vp, u32, vp]
     L.swiftprune_topk_select.restype = i32
     L.swiftprune_compact_nm.argtypes = [vp, i64, i64, i64, i32, vp, i32, i32, vp, vp, vp]
@@ -313,6 +319,41 @@ def swiftprune_calibrate_la(W, hr, target_sparsity: float, tolerance: float = 1e
     if code not in (SP_OK, SP_ERANGE):
         _check(code, "swiftprune_calibrate_la")
     return la.value, ach.value, code == SP_OK
+
+
+def swiftprune_la_workspace_bytes() -> int:
+    return int(load_library().swiftprune_la_workspace_bytes())
+
+
+def swiftprune_calibrate_la_device(W, hr, target_sparsity: float, la_out, pruned_out=None, status_out=None,
+                                   alpha: float = 0.125, beta: float = 0.125, workspace=None, stream=None):
+    """la for a target pruned fraction, computed on the stream and left in la_out (float32 GPU tensor [1]);
+    pruned_out (int64 [1]) and status_out (int32 [1]) are optional GPU tensors.  No synchronisation."""
+    import torch
+    ptr, out, n_in, ldw, dt = _matrix(W)
+    need = swiftprune_la_workspace_bytes()
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=W.device)
+    code = load_library().swiftprune_calibrate_la_device(
+        ptr, out, n_in, ldw, dt, _vec(hr, torch.float32, n_in, "hr"), float(alpha), float(beta),
+        float(target_sparsity), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+        _vec(la_out, torch.float32, 1, "la_out"), _vec(pruned_out, torch.int64, 1, "pruned_out"),
+        _vec(status_out, torch.int32, 1, "status_out"), _stream(stream))
+    _check(code, "swiftprune_calibrate_la_device")
+    return workspace
+
+
+def swiftprune_score_select_la(W, hr, la_dev, keep_mask, alpha: float = 0.125, beta: float = 0.125,
+                               row_pruned=None, flags: int = 0, stream=None):
+    """swiftprune_score_select with la read from a float32 GPU tensor [1] when the kernel runs."""
+    import torch
+    ptr, out, n_in, ldw, dt = _matrix(W)
+    words = (n_in + 31) // 32
+    code = load_library().swiftprune_score_select_la(
+        ptr, out, n_in, ldw, dt, _vec(hr, torch.float32, n_in, "hr"), float(alpha), float(beta),
+        _vec(la_dev, torch.float32, 1, "la_dev"), _vec(keep_mask, torch.int32, out * words, "keep_mask"),
+        _vec(row_pruned, torch.int32, out, "row_pruned"), int(flags), _stream(stream))
+    _check(code, "swiftprune_score_select_la")
 
 
 def swiftprune_topk_select(W, hr, keep_mask, k_per_row=None, k_uniform: int = 0, flags: int = 0, stream=None):

@@ -261,6 +261,49 @@ int swiftprune_calibrate_la(const void* W, int64_t out, int64_t in, int64_t ldw,
     return status == 0 ? SP_OK : SP_ERANGE;
 }
 
+size_t swiftprune_la_workspace_bytes(void) { return sp::la_workspace_bytes(); }
+
+int swiftprune_calibrate_la_device(const void* W, int64_t out, int64_t in, int64_t ldw, sp_dtype dt,
+                                   const float* hr, float alpha, float beta, float target_sparsity,
+                                   void* workspace, size_t workspace_bytes, float* la_device,
+                                   unsigned long long* pruned_device, int* status_device, void* hip_stream) {
+    if (W == nullptr || hr == nullptr || workspace == nullptr || la_device == nullptr) return SP_EINVAL;
+    if (out <= 0 || in <= 0 || ldw < in || !dtype_ok((int)dt)) return SP_EINVAL;
+    if (!(alpha > 0.0f && alpha <= 1.0f) || !(beta > 0.0f && beta <= 1.0f)) return SP_EINVAL;
+    if (!(target_sparsity > 0.0f && target_sparsity < 1.0f)) return SP_EINVAL;
+    if (reinterpret_cast<uintptr_t>(W) % elem_size((int)dt) != 0) return SP_EINVAL;
+    if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0 || reinterpret_cast<uintptr_t>(la_device) % 4 != 0 ||
+        reinterpret_cast<uintptr_t>(pruned_device) % 8 != 0 || reinterpret_cast<uintptr_t>(status_device) % 4 != 0)
+        return SP_EINVAL;
+    if (workspace_bytes < sp::la_workspace_bytes()) return SP_ENOSPC;
+    const double total = (double)out * (double)in;
+    double k = floor((double)target_sparsity * total + 0.5);
+    if (k > total - 1.0) k = total - 1.0;
+    const bool vec = weight_vec_ok(W, in, ldw, (int)dt, hr, nullptr);
+    const sp::EwmaConsts c = sp::make_ewma_consts(alpha, beta, 0.0f);
+    const hipError_t e = sp::launch_calibrate_la_device(W, out, in, ldw, (int)dt, vec, hr, c, (unsigned long long)k,
+                                                        workspace, la_device, pruned_device, status_device,
+                                                        static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? SP_OK : SP_EHIP;
+}
+
+int swiftprune_score_select_la(const void* W, int64_t out, int64_t in, int64_t ldw, sp_dtype dt, const float* hr,
+                               float alpha, float beta, const float* la_device, uint32_t* keep_mask,
+                               int32_t* row_pruned, uint32_t flags, void* hip_stream) {
+    if (W == nullptr || hr == nullptr || keep_mask == nullptr || la_device == nullptr) return SP_EINVAL;
+    if (out <= 0 || in <= 0 || ldw < in || !dtype_ok((int)dt)) return SP_EINVAL;
+    if (flags & ~SP_APPLY_INPLACE) return SP_EINVAL;
+    if (!(alpha > 0.0f && alpha <= 1.0f) || !(beta > 0.0f && beta <= 1.0f)) return SP_EINVAL;
+    if (reinterpret_cast<uintptr_t>(W) % elem_size((int)dt) != 0 || reinterpret_cast<uintptr_t>(la_device) % 4 != 0)
+        return SP_EINVAL;
+    const bool vec = weight_vec_ok(W, in, ldw, (int)dt, hr, nullptr);
+    sp::EwmaConsts c = sp::make_ewma_consts(alpha, beta, 0.0f);
+    c.la_dev = la_device;
+    const hipError_t e = sp::launch_ewma_scan(W, out, in, ldw, (int)dt, vec, hr, c, keep_mask, row_pruned, nullptr,
+                                              (flags & SP_APPLY_INPLACE) != 0, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? SP_OK : SP_EHIP;
+}
+
 int swiftprune_topk_select(const void* W, int64_t out, int64_t in, int64_t ldw, sp_dtype dt,
                            const float* hr, const int32_t* k_per_row, int64_t k_uniform,
                            uint32_t* keep_mask, uint32_t flags, void* hip_stream) {

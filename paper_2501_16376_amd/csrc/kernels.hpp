@@ -51,6 +51,7 @@ struct EwmaConsts {
     float B_pow[9];     // (1-beta)^k
     double A8_sq[7];    // ((1-alpha)^8)^(2^i), i = 0..6
     double B8_sq[7];
+    const float* la_dev;  // nullable: when set, la is read from device memory by the kernel (la, thr_scale unused)
 };
 EwmaConsts make_ewma_consts(float alpha, float beta, float la);
 
@@ -77,6 +78,11 @@ hipError_t launch_ewma_trace(const void* W, int64_t out, int64_t in, int64_t ldw
 hipError_t launch_count_pruned(const void* W, int64_t out, int64_t in, int64_t ldw, int dt, bool vec,
                                const float* hr, const EwmaConsts& c, const float* la, int n_la,
                                unsigned long long* counts, hipStream_t stream);
+size_t la_workspace_bytes();
+hipError_t launch_calibrate_la_device(const void* W, int64_t out, int64_t in, int64_t ldw, int dt, bool vec,
+                                      const float* hr, const EwmaConsts& c, unsigned long long target_count,
+                                      void* workspace, float* la_dev, unsigned long long* pruned_dev,
+                                      int* status_dev, hipStream_t stream);
 hipError_t run_calibrate_la(const void* W, int64_t out, int64_t in, int64_t ldw, int dt, bool vec,
                             const float* hr, const EwmaConsts& c, float target, float tolerance,
                             float la_lo, float la_hi, unsigned long long* counts_dev, float* la_out,

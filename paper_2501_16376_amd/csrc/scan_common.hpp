@@ -25,6 +25,15 @@ namespace sp {
 constexpr int kScanWaves = 4;  // rows per workgroup (one wavefront each)
 constexpr int kPrefetch = 4;   // row segments (16-byte loads per lane) in flight per wavefront
 
+// la and the scaled threshold factor (1-alpha) la beta, from the launch constants or, when the caller left
+// la in device memory (calibrated on the same stream), from there; the product is formed in double and
+// rounded once, exactly as the host does it
+__device__ __forceinline__ float ewma_la(const EwmaConsts& c) { return c.la_dev != nullptr ? c.la_dev[0] : c.la; }
+__device__ __forceinline__ float ewma_thr_scale(const EwmaConsts& c) {
+    if (c.la_dev == nullptr) return c.thr_scale;
+    return (float)((double)c.A_pow[1] * (double)c.la_dev[0] * (double)c.beta);
+}
+
 struct ScanLaneConsts {
     float shift;   // m^lane          : weight of the carried-in state at this lane
     float cross15; // m^((lane&15)+1) : weight of the previous 16-lane row's total

@@ -23,7 +23,7 @@ __global__ __launch_bounds__(kScanWaves* kWave) void ewma_scan_kernel(
     if (row >= out) return;  // whole wavefront leaves together
 
     const int64_t mask_words = (in + 31) >> 5;
-    const float neg_la = -c.la;
+    const float neg_la = -ewma_la(c);
     int pruned = 0;
 
     ewma_walk_row<DT, VEC>(W, row, in, ldw, hr, c, lane, scores,
@@ -66,6 +66,7 @@ EwmaConsts make_ewma_consts(float alpha, float beta, float la) {
     c.alpha = alpha;
     c.beta = beta;
     c.la = la;
+    c.la_dev = nullptr;
     const double A = (double)(1.0f - alpha);  // the decay as the fp32 walk sees it
     const double B = (double)(1.0f - beta);
     c.inv_alpha = (float)(1.0 / (double)alpha);

@@ -166,6 +166,7 @@ __global__ __launch_bounds__(kTeamThreads) void ewma_team_kernel(
     const ScanLaneConsts ce = make_lane_consts(c.A8_sq, lane);
     const ScanLaneConsts cd = make_lane_consts(c.B8_sq, lane);
     const float A = c.A_pow[1], B = c.B_pow[1];
+    const float thr_scale = ewma_thr_scale(c);
     const float A512 = (float)c.A8_sq[6], B512 = (float)c.B8_sq[6];
     // entry weight of a run's s-th segment at this lane, and of a whole run
     float shift_x[kSegs], shift_y[kSegs];
@@ -290,10 +291,10 @@ __global__ __launch_bounds__(kTeamThreads) void ewma_team_kernel(
             bool prune[8];
             // the row's first weight is never pruned (est starts at its score, dev at 0); in scaled form
             // that equality is only approximate, so it is stated
-            prune[0] = (x[s][0] > c.thr_scale * yin) && q0 != 0;
+            prune[0] = (x[s][0] > thr_scale * yin) && q0 != 0;
 #pragma unroll
             for (int k = 1; k < 8; ++k)
-                prune[k] = x[s][k] > c.thr_scale * fmaf(c.B_pow[k], yin, y[s][k - 1]);
+                prune[k] = x[s][k] > thr_scale * fmaf(c.B_pow[k], yin, y[s][k - 1]);
             const uint32_t gone = pack_bits8(prune);  // bit k = prune[k]
             const uint32_t keep = on ? (gone ^ 0xffu) : 0u;
             pruned += on ? __popc(gone) : 0;

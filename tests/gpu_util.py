@@ -32,12 +32,32 @@ def differing_bits(mask_a: np.ndarray, mask_b: np.ndarray, n: int):
 
 
 TOL = 1e-5   # relative distance between a score and its threshold within which a decision may differ
+ULPS = 8     # ... or this many fp32 units in the last place of the larger of the threshold's two terms
+
+
+def decision_open(L, thr, est_prev, dev_prev, la):
+    """True where the rounding-level rule leaves a decision open.  The threshold is est - la*dev; the scan
+    kernels evaluate est and dev in another addition order than the sequential fp32 walk, which moves each
+    by a few units in the last place.  Where the two terms do not cancel (every la of the paper's table:
+    thr is a good part of est) that is far inside TOL relative to the threshold; where they nearly cancel
+    (la around 1 and above, the ratios below 50 % that the paper's table does not cover) the threshold is
+    small against its terms and the same absolute error is a larger relative one, so the band is stated in
+    units of the terms themselves."""
+    L = np.asarray(L, dtype=np.float64)
+    thr = np.asarray(thr, dtype=np.float64)
+    gap = np.abs(L - thr)
+    rel_ok = gap <= TOL * np.maximum(np.abs(L), np.abs(thr))
+    terms = np.maximum(np.abs(np.asarray(est_prev, dtype=np.float32)),
+                       np.abs(np.float32(la) * np.asarray(dev_prev, dtype=np.float32)))
+    ulp_ok = gap <= ULPS * np.spacing(terms.astype(np.float32)).astype(np.float64)
+    return rel_ok | ulp_ok
 
 
 def check_ewma_mask(orc, W_host, hr, alpha, beta, la, mask_gpu, cnt_gpu=None):
     """Compare a GPU EWMA mask with the oracle's.  A bit may differ only where the oracle's score is
-    within TOL (relative) of the oracle's threshold for that element.  Returns the number of such
-    differences; raises on any other difference."""
+    within TOL (relative) of the oracle's threshold for that element, or within ULPS units in the last
+    place of the threshold's terms (decision_open).  Returns the number of such differences; raises on
+    any other difference."""
     n = W_host.shape[1]
     mask_o, cnt_o, _ = orc.ewma_select(W_host, hr, alpha, beta, la)
     diffs = differing_bits(mask_gpu, mask_o, n)
@@ -51,9 +71,9 @@ def check_ewma_mask(orc, W_host, hr, alpha, beta, la, mask_gpu, cnt_gpu=None):
             if q == 0:
                 raise AssertionError(f"row {r}: element 0 differs (it is never pruned)")
             thr = np.float32(est[q - 1]) - np.float32(la) * np.float32(dev[q - 1])
-            scale = max(abs(float(L[q])), abs(float(thr)))
-            if not abs(float(L[q]) - float(thr)) <= TOL * scale:
-                raise AssertionError(f"mask differs at ({r},{q}): L={L[q]!r} thr={thr!r}, not within {TOL} relative")
+            if not decision_open(L[q], thr, est[q - 1], dev[q - 1], la):
+                raise AssertionError(f"mask differs at ({r},{q}): L={L[q]!r} thr={thr!r} est={est[q - 1]!r}, "
+                                     f"not within {TOL} relative nor {ULPS} ulp of the threshold's terms")
         if cnt_gpu is not None:
             assert abs(int(cnt_gpu[r]) - int(cnt_o[r])) <= len(qs)
     if cnt_gpu is not None:
@@ -72,6 +92,5 @@ def near_threshold_count(orc, W_host, hr, alpha, beta, la):
         L = sc[r]
         _, est, dev = orc.ewma_row(L, alpha, beta, la, precision="f32")
         thr = est[:-1] - np.float32(la) * dev[:-1]
-        scale = np.maximum(np.abs(L[1:]), np.abs(thr))
-        total += int(np.sum(np.abs(L[1:].astype(np.float64) - thr.astype(np.float64)) <= TOL * scale))
+        total += int(np.sum(decision_open(L[1:], thr, est[:-1], dev[:-1], la)))
     return total

@@ -169,6 +169,21 @@ def test_argument_checks_do_not_launch(lib):
     assert cal(p, 8, 8, 8, 1, p, 0.125, 0.125, 0.3, 0.0, -8.0, 8.0, p, C.byref(la_o), C.byref(ach_o), None) == E
     assert cal(p, 8, 8, 8, 1, p, 0.125, 0.125, 0.3, 1e-3, 2.0, 1.0, p, C.byref(la_o), C.byref(ach_o), None) == E
     assert cal(p, 8, 8, 8, 1, p, 0.125, 0.125, 0.3, 1e-3, -8.0, 8.0, None, C.byref(la_o), C.byref(ach_o), None) == E
+    cd = lib.swiftprune_calibrate_la_device
+    wsb = lib.swiftprune_la_workspace_bytes()
+    assert 8192 <= wsb <= 65536
+    assert cd(None, 8, 8, 8, 1, p, 0.125, 0.125, 0.3, p, wsb, p, None, None, None) == E
+    assert cd(p, 8, 8, 8, 1, p, 0.125, 0.125, 0.0, p, wsb, p, None, None, None) == E
+    assert cd(p, 8, 8, 8, 1, p, 0.125, 0.125, 1.0, p, wsb, p, None, None, None) == E
+    assert cd(p, 8, 8, 8, 1, p, 0.125, 0.125, 0.3, p + 8, wsb, p, None, None, None) == E   # workspace alignment
+    assert cd(p, 8, 8, 8, 1, p, 0.125, 0.125, 0.3, p, wsb, None, None, None, None) == E
+    assert cd(p, 8, 8, 8, 1, p, 0.125, 0.125, 0.3, p, wsb, p, p + 4, None, None) == E      # uint64 alignment
+    assert cd(p, 8, 8, 8, 1, p, 0.125, 0.125, 0.3, p, 16, p, None, None, None) == binding.SP_ENOSPC
+    sl = lib.swiftprune_score_select_la
+    assert sl(p, 8, 8, 8, 1, p, 0.125, 0.125, None, p, None, 0, None) == E
+    assert sl(p, 8, 8, 8, 1, p, 0.125, 0.125, p, None, None, 0, None) == E
+    assert sl(p, 8, 8, 8, 1, p, 0.125, 0.125, p, p, None, 1, None) == E                    # strict-order flag not valid here
+    assert sl(p, 8, 8, 8, 1, p, 0.0, 0.125, p, p, None, 0, None) == E
     tk = lib.swiftprune_topk_select
     assert tk(None, 8, 8, 8, 1, p, None, 4, p, 0, None) == E
     assert tk(p, 8, 8, 8, 1, p, None, 4, None, 0, None) == E

@@ -79,6 +79,53 @@ def test_calibrate_la_hits_targets(orc, gpu):
     assert not reached and la == 0.0
 
 
+@pytest.mark.parametrize("out,n,dtype,targets", [
+    (512, 4096, "bf16", (0.9, 0.7, 0.5, 0.4, 0.3, 0.2, 0.1)),
+    (1024, 8192, "bf16", (0.3, 0.5, 0.7)),          # the k / v shape of the 70B-shaped model, the sweep of its config
+    (37, 1001, "f32", (0.25, 0.6)),                 # odd width: general kernels
+])
+def test_calibrate_la_on_device(orc, gpu, out, n, dtype, targets):
+    """la from the three-pass radix select on the device, never touching the host: evaluated by the oracle
+    it prunes the requested number of weights up to the decisions the rounding rule leaves open; the
+    selection that reads it from device memory equals the selection given the same la by value and
+    passes the threshold rule; it agrees with the host-driven search."""
+    import torch
+    from paper_2501_16376_amd import binding as b
+    from gpu_util import mask_to_host, check_ewma_mask, near_threshold_count
+    Wh, hr, W, hr_dev = _inputs(orc, gpu, out, n, 256, seed=3 * out + n, dtype=dtype)
+    la_dev = torch.full((1,), float("nan"), dtype=torch.float32, device=gpu)
+    pruned_dev = torch.full((1,), -1, dtype=torch.int64, device=gpu)
+    status_dev = torch.full((1,), -1, dtype=torch.int32, device=gpu)
+    mask = torch.empty((out, (n + 31) // 32), dtype=torch.int32, device=gpu)
+    mask2 = torch.empty_like(mask)
+    cnt = torch.empty(out, dtype=torch.int32, device=gpu)
+    cnt2 = torch.empty_like(cnt)
+    ws = None
+    for target in targets:
+        say(f"[case] device la out={out} in={n} {dtype} target={target}")
+        k = int(np.floor(np.float32(target).astype(np.float64) * out * n + 0.5))
+        ws = b.swiftprune_calibrate_la_device(W, hr_dev, target, la_dev, pruned_dev, status_dev, workspace=ws)
+        b.swiftprune_score_select_la(W, hr_dev, la_dev, mask, row_pruned=cnt)      # same stream, no host in between
+        torch.cuda.synchronize()
+        la = float(la_dev.item())
+        assert int(status_dev.item()) == 0 and np.isfinite(la)
+        assert 0 <= k - int(pruned_dev.item()) <= 2                  # fewer only when critical multipliers tie
+        slack = near_threshold_count(orc, Wh, hr, A, B, la)
+        cnt_o = int(orc.ewma_select(Wh, hr, A, B, la)[1].sum())
+        assert abs(cnt_o - k) <= slack + 2, (target, la, cnt_o, k, slack)
+        check_ewma_mask(orc, Wh, hr, A, B, la, mask_to_host(mask), cnt.cpu().numpy())
+        b.swiftprune_score_select(W, hr_dev, mask2, la=la, row_pruned=cnt2)
+        torch.cuda.synchronize()
+        assert torch.equal(mask, mask2) and torch.equal(cnt, cnt2)
+        la_h, ach_h, reached = b.swiftprune_calibrate_la(W, hr_dev, target, tolerance=1e-4)
+        assert reached and abs(la_h - la) <= 2e-3 * max(1.0, abs(la)), (la_h, la)
+        say(f"   la = {la:+.5f} prunes {cnt_o} of {out * n} (wanted {k}); host search {la_h:+.5f}")
+    # a count below the number of weights that are pruned for every la has no finite answer
+    b.swiftprune_calibrate_la_device(W, hr_dev, 2.0 / (out * n), la_dev, pruned_dev, status_dev, workspace=ws)
+    torch.cuda.synchronize()
+    assert int(status_dev.item()) == 1 and float(la_dev.item()) == pytest.approx(3.0e38, rel=1e-6)
+
+
 @pytest.mark.parametrize("out,n,dtype", [(64, 4096, "bf16"), (9, 1000, "bf16"), (17, 333, "f32"), (3, 40000, "bf16"), (21, 2000, "f16")])
 def test_topk_select_matches_sort(orc, gpu, out, n, dtype):
     """Radix-select masks equal the oracle's sort-based masks bit for bit (same factor), for per-row k,
