@@ -26,6 +26,9 @@ inline bool weight_vec_ok(const void* W, int64_t in, int64_t ldw, int dt, const 
            (scores == nullptr || aligned16(scores));
 }
 
+// the fast selection kernels number the rows of a launch with 32 bits (and add a grid stride to them)
+constexpr int64_t kMaxFastRows = (int64_t)1 << 30;
+
 const float kTableRatio[5] = {0.5f, 0.6f, 0.7f, 0.8f, 0.9f};
 const float kTableLa[5] = {0.5f, 0.2f, -0.2f, -0.9f, -1.5f};
 
@@ -122,7 +125,7 @@ int swiftprune_score_select(const void* W, int64_t out, int64_t in, int64_t ldw,
         e = sp::launch_ewma_sequential(W, out, in, ldw, (int)dt, hr, p.alpha, p.beta, p.la, keep_mask,
                                        row_pruned, scores, apply, stream);
     } else {
-        const bool vec = weight_vec_ok(W, in, ldw, (int)dt, hr, scores);
+        const bool vec = out <= kMaxFastRows && weight_vec_ok(W, in, ldw, (int)dt, hr, scores);
         const sp::EwmaConsts c = sp::make_ewma_consts(p.alpha, p.beta, p.la);
         e = sp::launch_ewma_scan(W, out, in, ldw, (int)dt, vec, hr, c, keep_mask, row_pruned, scores,
                                  apply, stream);
@@ -132,10 +135,13 @@ int swiftprune_score_select(const void* W, int64_t out, int64_t in, int64_t ldw,
 
 static bool group_ok(const sp_matrix* mats, int n_mats, int64_t in, int dt) {
     if (mats == nullptr || n_mats < 1 || n_mats > SP_MAX_GROUP || in <= 0 || !dtype_ok(dt)) return false;
+    int64_t rows = 0;
     for (int j = 0; j < n_mats; ++j) {
         const sp_matrix& m = mats[j];
         if (m.W == nullptr || m.keep_mask == nullptr || m.out <= 0 || m.ldw < in) return false;
         if (reinterpret_cast<uintptr_t>(m.W) % elem_size(dt) != 0) return false;
+        rows += m.out;
+        if (rows > kMaxFastRows) return false;
     }
     return true;
 }
@@ -147,7 +153,7 @@ static sp::RowGroups make_groups(const sp_matrix* mats, int n_mats) {
     for (int j = 0; j < sp::kMaxGroup; ++j) {
         const sp_matrix& m = mats[j < n_mats ? j : n_mats - 1];
         if (j < n_mats) end += m.out;
-        g.row_end[j] = end;
+        g.row_end[j] = (int32_t)end;
         g.W[j] = m.W;
         g.ldw[j] = m.ldw;
         g.keep_mask[j] = m.keep_mask;
@@ -296,7 +302,7 @@ int swiftprune_score_select_la(const void* W, int64_t out, int64_t in, int64_t l
     if (!(alpha > 0.0f && alpha <= 1.0f) || !(beta > 0.0f && beta <= 1.0f)) return SP_EINVAL;
     if (reinterpret_cast<uintptr_t>(W) % elem_size((int)dt) != 0 || reinterpret_cast<uintptr_t>(la_device) % 4 != 0)
         return SP_EINVAL;
-    const bool vec = weight_vec_ok(W, in, ldw, (int)dt, hr, nullptr);
+    const bool vec = out <= kMaxFastRows && weight_vec_ok(W, in, ldw, (int)dt, hr, nullptr);
     sp::EwmaConsts c = sp::make_ewma_consts(alpha, beta, 0.0f);
     c.la_dev = la_device;
     const hipError_t e = sp::launch_ewma_scan(W, out, in, ldw, (int)dt, vec, hr, c, keep_mask, row_pruned, nullptr,
@@ -327,7 +333,7 @@ int swiftprune_nm_select(const void* W, int64_t out, int64_t in, int64_t ldw, sp
     if (n_keep <= 0 || n_keep >= m_group || in % m_group != 0) return SP_EINVAL;
     if (flags & ~SP_APPLY_INPLACE) return SP_EINVAL;
     if (reinterpret_cast<uintptr_t>(W) % elem_size((int)dt) != 0) return SP_EINVAL;
-    const bool vec = weight_vec_ok(W, in, ldw, (int)dt, hr, scores);
+    const bool vec = out <= kMaxFastRows && weight_vec_ok(W, in, ldw, (int)dt, hr, scores);
     const hipError_t e =
         sp::launch_nm_select(W, out, in, ldw, (int)dt, vec, hr, n_keep, m_group, keep_mask, scores,
                              (flags & SP_APPLY_INPLACE) != 0, static_cast<hipStream_t>(hip_stream));

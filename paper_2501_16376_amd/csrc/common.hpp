@@ -221,24 +221,111 @@ __device__ __forceinline__ float score_of(float w, float factor) {
     return __fmul_rn(w2, factor);
 }
 
+// Packs eight per-lane decisions into bits 0..7 (bit k = p[k]) with one add-with-carry each:
+// acc <- 2 acc + p[k], k = 7 .. 0, the decision entering as the carry.
+__device__ __forceinline__ uint32_t pack_bits8(const bool* p) {
+    uint32_t acc = 0u;
+    const uint64_t b0 = __builtin_amdgcn_ballot_w64(p[0]), b1 = __builtin_amdgcn_ballot_w64(p[1]),
+                   b2 = __builtin_amdgcn_ballot_w64(p[2]), b3 = __builtin_amdgcn_ballot_w64(p[3]),
+                   b4 = __builtin_amdgcn_ballot_w64(p[4]), b5 = __builtin_amdgcn_ballot_w64(p[5]),
+                   b6 = __builtin_amdgcn_ballot_w64(p[6]), b7 = __builtin_amdgcn_ballot_w64(p[7]);
+    asm("v_addc_co_u32 %0, vcc, %0, %0, %8\n\t"
+        "v_addc_co_u32 %0, vcc, %0, %0, %7\n\t"
+        "v_addc_co_u32 %0, vcc, %0, %0, %6\n\t"
+        "v_addc_co_u32 %0, vcc, %0, %0, %5\n\t"
+        "v_addc_co_u32 %0, vcc, %0, %0, %4\n\t"
+        "v_addc_co_u32 %0, vcc, %0, %0, %3\n\t"
+        "v_addc_co_u32 %0, vcc, %0, %0, %2\n\t"
+        "v_addc_co_u32 %0, vcc, %0, %0, %1"
+        : "+v"(acc)
+        : "s"(b0), "s"(b1), "s"(b2), "s"(b3), "s"(b4), "s"(b5), "s"(b6), "s"(b7)
+        : "vcc");
+    return acc;
+}
+
+// eight weights of a lane as fp32, kept unpacked until they are stored again
+template <int DT>
+struct Unpacked8 {
+    float w[8];
+    __device__ __forceinline__ void unpack(const Chunk8<DT>& c) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) w[k] = c.get(k);
+    }
+    // pruned entries become +0; bf16 / fp16 pairs are re-packed with one byte permute each
+    __device__ __forceinline__ void store_pruned(void* W, int64_t elem, const bool* prune) const {
+        uint32_t z[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) z[k] = prune[k] ? 0u : __float_as_uint(w[k]);
+        store_words(W, elem, z);
+    }
+    __device__ __forceinline__ void store_words(void* W, int64_t elem, const uint32_t* z) const {
+        if (DT == kF32) {
+            u32x4* p = reinterpret_cast<u32x4*>(static_cast<float*>(W) + elem);
+            u32x4 a, b;
+            a.x = z[0]; a.y = z[1]; a.z = z[2]; a.w = z[3];
+            b.x = z[4]; b.y = z[5]; b.z = z[6]; b.w = z[7];
+            __builtin_nontemporal_store(a, p);
+            __builtin_nontemporal_store(b, p + 1);
+        } else {
+            uint32_t pk[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (DT == kBF16) {
+                    // high halves of the two fp32 patterns: bytes 2,3 of z[2j] below bytes 2,3 of z[2j+1]
+                    pk[j] = __builtin_amdgcn_perm(z[2 * j + 1], z[2 * j], 0x07060302u);
+                } else {
+                    const _Float16 lo = (_Float16)__uint_as_float(z[2 * j]);   // exact: the value came from binary16
+                    const _Float16 hi = (_Float16)__uint_as_float(z[2 * j + 1]);
+                    pk[j] = (uint32_t)__builtin_bit_cast(uint16_t, lo) | ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16);
+                }
+            }
+            u32x4 v;
+            v.x = pk[0]; v.y = pk[1]; v.z = pk[2]; v.w = pk[3];
+            __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(static_cast<uint16_t*>(W) + elem));
+        }
+    }
+};
+
 // Which matrix of a group a consecutively numbered row belongs to, and its row number inside that matrix.
-// Wave-uniform input gives wave-uniform results (scalar selects).
+// The group description is a kernel argument, i.e. it sits in memory: the matrix index is found with a few
+// compares and its entries are fetched by index (scalar loads when the row is wave-uniform).  Unused entries
+// of row_end repeat the total, so a valid row never compares above them.  Row numbers are 32-bit: the scalar
+// unit has no 64-bit ordered compare.
 template <class Groups>
 struct RowOwner {
     void* W;
     int64_t ldw, row;
     uint32_t* keep_mask;
     int32_t* row_pruned;
-    __device__ __forceinline__ RowOwner(const Groups& g, int64_t global_row) {
-        W = g.W[0]; ldw = g.ldw[0]; keep_mask = g.keep_mask[0]; row_pruned = g.row_pruned[0];
-        row = global_row;
+    int item;
+    int32_t first, end;  // global numbers of the matrix's first row and of the row behind its last
+    __device__ __forceinline__ RowOwner(const Groups& g, int32_t global_row) {
+        item = 0;
 #pragma unroll
-        for (int j = 1; j < (int)(sizeof(g.row_end) / sizeof(g.row_end[0])); ++j) {
-            if (j < g.n && global_row >= g.row_end[j - 1]) {
-                W = g.W[j]; ldw = g.ldw[j]; keep_mask = g.keep_mask[j]; row_pruned = g.row_pruned[j];
-                row = global_row - g.row_end[j - 1];
-            }
+        for (int j = 1; j < (int)(sizeof(g.row_end) / sizeof(g.row_end[0])); ++j)
+            item += global_row >= g.row_end[j - 1] ? 1 : 0;
+        first = item > 0 ? g.row_end[item - 1] : 0;
+        bind(g, global_row);
+    }
+    // moves on to a later row (never back): one compare unless the row belongs to a later matrix
+    __device__ __forceinline__ void seek(const Groups& g, int32_t global_row) {
+        if (global_row >= end) {
+            while (global_row >= g.row_end[item]) ++item;
+            first = g.row_end[item - 1];
+            bind(g, global_row);
+        } else {
+            row = (int64_t)(global_row - first);
         }
+    }
+
+  private:
+    __device__ __forceinline__ void bind(const Groups& g, int32_t global_row) {
+        end = g.row_end[item];
+        W = g.W[item];
+        ldw = g.ldw[item];
+        keep_mask = g.keep_mask[item];
+        row_pruned = g.row_pruned[item];
+        row = (int64_t)(global_row - first);
     }
 };
 

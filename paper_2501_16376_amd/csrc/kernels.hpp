@@ -34,12 +34,12 @@ hipError_t launch_layer_stats(const void* X, int64_t tokens, int64_t in, int64_t
 constexpr int kMaxGroup = 8;
 struct RowGroups {
     int n;                          // matrices in use (1 .. kMaxGroup)
-    int64_t row_end[kMaxGroup];     // running totals of the row counts; unused entries repeat the last total
+    int32_t row_end[kMaxGroup];     // running totals of the row counts (all rows together < 2^31); unused entries repeat the last total
     void* W[kMaxGroup];
     int64_t ldw[kMaxGroup];
     uint32_t* keep_mask[kMaxGroup];
     int32_t* row_pruned[kMaxGroup];  // nullable per matrix
-    __host__ __device__ int64_t total() const { return row_end[kMaxGroup - 1]; }
+    __host__ __device__ int32_t total() const { return row_end[kMaxGroup - 1]; }
 };
 
 // ---- steps 2+3: EWMA selection ----

@@ -193,7 +193,7 @@ BandPlan make_band_plan(int64_t out, int64_t in, int target_groups, int unroll =
     return p;
 }
 
-template <int DT, int M, int U>
+template <int DT, int M, int U, bool GROUPED>
 __global__ __launch_bounds__(kColThreads) void nm_select_band_kernel(
     const RowGroups g, int64_t in, const float* __restrict__ hr, int n_prune, float* __restrict__ scores,
     int apply, int strip_units) {
@@ -201,46 +201,51 @@ __global__ __launch_bounds__(kColThreads) void nm_select_band_kernel(
     const int64_t unit = (int64_t)blockIdx.x * strip_units + threadIdx.x;
     const int64_t q0 = unit * 8;
     const bool active = (int)threadIdx.x < strip_units && q0 < in;  // in % 8 == 0 on this path
+    const int64_t q_ld = active ? q0 : 0;  // lanes without columns read the row's start and store nothing
     const int64_t mask_words = (in + 31) >> 5;
-    const int64_t step = (int64_t)gridDim.y * U;
-    const int64_t out = g.total();  // rows of all matrices of the group, numbered consecutively
+    const int32_t step = (int32_t)(gridDim.y * U);
+    const int32_t out = g.total();  // rows of all matrices of the group, numbered consecutively (< 2^31)
 
     Factor8 f;
-    if (active) f.load_vec(hr, q0); else f.load_elems(hr, 0, 0);
+    f.load_vec(hr, q_ld);
 
-    auto fetch = [&](Chunk8<DT>* w, int64_t r0) {
+    auto fetch = [&](Chunk8<DT>* w, int32_t r0) {
+        if (r0 >= out) return;  // uniform, like every row test below: the lookups stay on the scalar unit
+        RowOwner<RowGroups> own(g, GROUPED ? r0 : 0);
 #pragma unroll
         for (int j = 0; j < U; ++j) {
-            if (active && r0 + j < out) {
-                const RowOwner<RowGroups> own(g, r0 + j);
-                w[j].load_vec(own.W, own.row * own.ldw + q0);
-            } else {
-                w[j].zero();
+            if (r0 + j < out) {
+                if (GROUPED) own.seek(g, r0 + j);
+                const int64_t row = GROUPED ? own.row : (int64_t)(r0 + j);
+                w[j].load_vec(own.W, row * own.ldw + q_ld);
             }
         }
     };
-    auto work = [&](Chunk8<DT>* w, int64_t r0) {
+    auto work = [&](Chunk8<DT>* w, int32_t r0) {
+        RowOwner<RowGroups> own(g, GROUPED ? r0 : 0);
 #pragma unroll
         for (int j = 0; j < U; ++j) {
             if (r0 + j >= out) break;  // uniform over the workgroup
-            const RowOwner<RowGroups> own(g, r0 + j);
+            if (GROUPED) own.seek(g, r0 + j);
+            const int64_t row = GROUPED ? own.row : (int64_t)(r0 + j);
             float L[8];
 #pragma unroll
             for (int k = 0; k < 8; ++k) L[k] = score_of(w[j].get(k), f.v[k]);
+            if (scores != nullptr && active) store8(scores + (int64_t)(r0 + j) * in + q0, L, true, 8);  // single matrix only
             uint32_t keep = (M == 16) ? nm_keep_bits16(L, n_prune, lane) : nm_keep_bits<(M == 16 ? 8 : M)>(L, n_prune);
-            if (!active) keep = 0u;
-            if (scores != nullptr && active) store8(scores + (r0 + j) * in + q0, L, true, 8);  // single matrix only
-            const uint32_t word = quad_gather_bytes(keep, lane);
-            if ((lane & 3) == 0 && active) own.keep_mask[own.row * mask_words + (q0 >> 5)] = word;
             if (apply && active) {
                 w[j].apply(keep);
-                w[j].store_vec_nt(own.W, own.row * own.ldw + q0);
+                w[j].store_vec_nt(own.W, row * own.ldw + q0);
             }
+            if (!active) keep = 0u;
+            const uint32_t word = quad_gather_bytes(keep, lane);
+            if ((lane & 3) == 0 && active) own.keep_mask[row * mask_words + (q0 >> 5)] = word;
         }
     };
     // two batches alternate: while one is worked on, the loads of the next are in flight
+    // (row numbers stay below 2^31 - step: the launcher refuses larger groups)
     Chunk8<DT> a[U], b[U];
-    int64_t r0 = (int64_t)blockIdx.y * U;
+    int32_t r0 = (int32_t)(blockIdx.y * U);
     fetch(a, r0);
     while (r0 < out) {
         fetch(b, r0 + step);
@@ -304,18 +309,25 @@ __global__ __launch_bounds__(kColThreads) void apply_band_kernel(void* __restric
 constexpr int kApplyBandGroups = 512;
 constexpr int kSelectBandGroups = 768;
 
-template <int DT, int M>
-static hipError_t launch_nm_band(const RowGroups& g, int64_t in, const float* hr, int n_prune, float* scores,
-                                 int apply, int target_groups, hipStream_t stream, int unroll = 4) {
+template <int DT, int M, bool GROUPED>
+static hipError_t launch_nm_band_t(const RowGroups& g, int64_t in, const float* hr, int n_prune, float* scores,
+                                   int apply, int target_groups, hipStream_t stream, int unroll) {
     const BandPlan p = make_band_plan(g.total(), in, target_groups, unroll);
     const dim3 grid((unsigned)p.nstrips, (unsigned)p.splits), block(kColThreads);
     switch (p.unroll) {
-        case 8: hipLaunchKernelGGL((nm_select_band_kernel<DT, M, 8>), grid, block, 0, stream, g, in, hr, n_prune, scores, apply, p.strip_units); break;
-        case 4: hipLaunchKernelGGL((nm_select_band_kernel<DT, M, 4>), grid, block, 0, stream, g, in, hr, n_prune, scores, apply, p.strip_units); break;
-        case 2: hipLaunchKernelGGL((nm_select_band_kernel<DT, M, 2>), grid, block, 0, stream, g, in, hr, n_prune, scores, apply, p.strip_units); break;
-        default: hipLaunchKernelGGL((nm_select_band_kernel<DT, M, 1>), grid, block, 0, stream, g, in, hr, n_prune, scores, apply, p.strip_units); break;
+        case 8: hipLaunchKernelGGL((nm_select_band_kernel<DT, M, 8, GROUPED>), grid, block, 0, stream, g, in, hr, n_prune, scores, apply, p.strip_units); break;
+        case 4: hipLaunchKernelGGL((nm_select_band_kernel<DT, M, 4, GROUPED>), grid, block, 0, stream, g, in, hr, n_prune, scores, apply, p.strip_units); break;
+        case 2: hipLaunchKernelGGL((nm_select_band_kernel<DT, M, 2, GROUPED>), grid, block, 0, stream, g, in, hr, n_prune, scores, apply, p.strip_units); break;
+        default: hipLaunchKernelGGL((nm_select_band_kernel<DT, M, 1, GROUPED>), grid, block, 0, stream, g, in, hr, n_prune, scores, apply, p.strip_units); break;
     }
     return hipGetLastError();
+}
+
+template <int DT, int M>
+static hipError_t launch_nm_band(const RowGroups& g, int64_t in, const float* hr, int n_prune, float* scores,
+                                 int apply, int target_groups, hipStream_t stream, int unroll = 4) {
+    return g.n > 1 ? launch_nm_band_t<DT, M, true>(g, in, hr, n_prune, scores, apply, target_groups, stream, unroll)
+                   : launch_nm_band_t<DT, M, false>(g, in, hr, n_prune, scores, apply, target_groups, stream, unroll);
 }
 
 template <int DT>

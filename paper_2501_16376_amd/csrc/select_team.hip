@@ -64,74 +64,12 @@ __device__ __forceinline__ void team_scan2(float& r0, float& r1, const ScanLaneC
 #undef SP_STEP
 }
 
-// Packs eight per-lane decisions into bits 0..7 (bit k = p[k]) with one add-with-carry each:
-// acc <- 2 acc + p[k], k = 7 .. 0, the decision entering as the carry.
-__device__ __forceinline__ uint32_t pack_bits8(const bool* p) {
-    uint32_t acc = 0u;
-    const uint64_t b0 = __builtin_amdgcn_ballot_w64(p[0]), b1 = __builtin_amdgcn_ballot_w64(p[1]),
-                   b2 = __builtin_amdgcn_ballot_w64(p[2]), b3 = __builtin_amdgcn_ballot_w64(p[3]),
-                   b4 = __builtin_amdgcn_ballot_w64(p[4]), b5 = __builtin_amdgcn_ballot_w64(p[5]),
-                   b6 = __builtin_amdgcn_ballot_w64(p[6]), b7 = __builtin_amdgcn_ballot_w64(p[7]);
-    asm("v_addc_co_u32 %0, vcc, %0, %0, %8\n\t"
-        "v_addc_co_u32 %0, vcc, %0, %0, %7\n\t"
-        "v_addc_co_u32 %0, vcc, %0, %0, %6\n\t"
-        "v_addc_co_u32 %0, vcc, %0, %0, %5\n\t"
-        "v_addc_co_u32 %0, vcc, %0, %0, %4\n\t"
-        "v_addc_co_u32 %0, vcc, %0, %0, %3\n\t"
-        "v_addc_co_u32 %0, vcc, %0, %0, %2\n\t"
-        "v_addc_co_u32 %0, vcc, %0, %0, %1"
-        : "+v"(acc)
-        : "s"(b0), "s"(b1), "s"(b2), "s"(b3), "s"(b4), "s"(b5), "s"(b6), "s"(b7)
-        : "vcc");
-    return acc;
-}
-
 // workgroup barrier that orders LDS traffic only: outstanding global loads and stores keep flying
 __device__ __forceinline__ void team_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
-
-// eight weights of a lane as fp32, kept unpacked until they are stored again
-template <int DT>
-struct Unpacked8 {
-    float w[8];
-    __device__ __forceinline__ void unpack(const Chunk8<DT>& c) {
-#pragma unroll
-        for (int k = 0; k < 8; ++k) w[k] = c.get(k);
-    }
-    // pruned entries become +0; bf16 / fp16 pairs are re-packed with one byte permute each
-    __device__ __forceinline__ void store_pruned(void* W, int64_t elem, const bool* prune) const {
-        uint32_t z[8];
-#pragma unroll
-        for (int k = 0; k < 8; ++k) z[k] = prune[k] ? 0u : __float_as_uint(w[k]);
-        if (DT == kF32) {
-            u32x4* p = reinterpret_cast<u32x4*>(static_cast<float*>(W) + elem);
-            u32x4 a, b;
-            a.x = z[0]; a.y = z[1]; a.z = z[2]; a.w = z[3];
-            b.x = z[4]; b.y = z[5]; b.z = z[6]; b.w = z[7];
-            __builtin_nontemporal_store(a, p);
-            __builtin_nontemporal_store(b, p + 1);
-        } else {
-            uint32_t pk[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if (DT == kBF16) {
-                    // high halves of the two fp32 patterns: bytes 2,3 of z[2j] below bytes 2,3 of z[2j+1]
-                    pk[j] = __builtin_amdgcn_perm(z[2 * j + 1], z[2 * j], 0x07060302u);
-                } else {
-                    const _Float16 lo = (_Float16)__uint_as_float(z[2 * j]);   // exact: the value came from binary16
-                    const _Float16 hi = (_Float16)__uint_as_float(z[2 * j + 1]);
-                    pk[j] = (uint32_t)__builtin_bit_cast(uint16_t, lo) | ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16);
-                }
-            }
-            u32x4 v;
-            v.x = pk[0]; v.y = pk[1]; v.z = pk[2]; v.w = pk[3];
-            __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(static_cast<uint16_t*>(W) + elem));
-        }
-    }
-};
 
 // grid = ceil(rows of all matrices / (4 / NW)), block = 256 (4 wavefronts).  Requires the 16-byte-vector layout
 // (W and hr 16-byte aligned, in % 8 == 0, ldw a multiple of 16 bytes) and alpha < 1.
@@ -148,7 +86,7 @@ __global__ __launch_bounds__(kTeamThreads) void ewma_team_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // uniform: the row lookup below stays scalar
     const int slot = wave / NW;  // which row of the workgroup
     const int part = wave % NW;  // which run of the row's spans
-    const int64_t global_row = (int64_t)blockIdx.x * kRowsPerGroup + slot;
+    const int32_t global_row = (int32_t)(blockIdx.x * kRowsPerGroup + slot);   // the launcher keeps the row total below 2^31
     const bool has_row = global_row < g.total();
     // a wavefront without a row (past the last one) still walks the loop and meets the barriers, with all
     // its lanes switched off
@@ -327,8 +265,7 @@ template <int DT, int NW>
 static hipError_t launch_team_t(const RowGroups& g, int64_t in, const float* hr, const EwmaConsts& c, bool apply,
                                 hipStream_t stream) {
     constexpr int rows = 4 / NW;
-    const int64_t groups = (g.total() + rows - 1) / rows;
-    if (groups > 0x7fffffff) return hipErrorInvalidValue;
+    const int64_t groups = ((int64_t)g.total() + rows - 1) / rows;
     hipLaunchKernelGGL((ewma_team_kernel<DT, NW>), dim3((unsigned)groups), dim3(kTeamThreads), 0, stream, g, in, hr, c,
                        apply ? 1 : 0);
     return hipGetLastError();
@@ -338,7 +275,7 @@ RowGroups single_matrix(const void* W, int64_t out, int64_t ldw, uint32_t* keep_
     RowGroups g;
     g.n = 1;
     for (int j = 0; j < kMaxGroup; ++j) {
-        g.row_end[j] = out;
+        g.row_end[j] = (int32_t)out;
         g.W[j] = const_cast<void*>(W);
         g.ldw[j] = ldw;
         g.keep_mask[j] = keep_mask;
