@@ -52,6 +52,10 @@ def parse():
     ap.add_argument("--layer-sweep", action="store_true",
                     help="also time every distinct layer shape of the block on its own (statistics + "
                          "selection/apply) and add the per-layer HBM fractions to the JSON line")
+    ap.add_argument("--tuning-sweep", action="store_true",
+                    help="instead of the benchmark: time the kernels of the 8B layer shapes under the library's "
+                         "launch-shape overrides (SWIFTPRUNE_STATS_PLAN, SWIFTPRUNE_SELECT_TEAM, "
+                         "SWIFTPRUNE_BAND_GROUPS) and print one line per setting")
     ap.add_argument("--prime", type=int, default=4,
                     help="untimed passes at the end of set-up, before the W warm-up steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -231,6 +235,9 @@ def main():
     T = args.tokens
     nm = None if args.mode == "unstructured" else tuple(int(x) for x in args.mode.split(":"))
     la = args.la
+    if args.tuning_sweep:
+        tuning_sweep(sp, synth, torch, dev, T, args.storage)
+        return
 
     t_setup = time.time()
     stack = Stack(sp, synth, torch, dev, args.model, args.blocks, T, args.storage)
@@ -355,6 +362,79 @@ def main():
     if cpu is not None:
         result["cpu_baseline"] = cpu
     print(json.dumps(result))
+
+
+def tuning_sweep(sp, synth, torch, dev, T, storage, reps=6):
+    """The evidence behind the built-in launch shapes: every kernel of the path on the 8B layer shapes under
+    the library's environment overrides, HIP events over `reps` launches on rotating buffers."""
+    stream = torch.cuda.current_stream()
+
+    def timed(fn, n):
+        fn(0)
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        ev[0].record(stream)
+        for i in range(n):
+            fn(i)
+        ev[1].record(stream)
+        torch.cuda.synchronize()
+        return ev[0].elapsed_time(ev[1]) / n * 1e3            # microseconds per launch
+
+    def say(kind, shape, setting, us, nbytes):
+        print(json.dumps({"kernel": kind, "shape": shape, "setting": setting, "us": round(us, 1),
+                          "TBps": round(nbytes / us / 1e6, 3), "hbm_frac": round(nbytes / us / 1e6 / 8.0, 4)}), flush=True)
+
+    for k in ("SWIFTPRUNE_STATS_PLAN", "SWIFTPRUNE_SELECT_TEAM", "SWIFTPRUNE_BAND_GROUPS"):
+        os.environ.pop(k, None)
+    # ---- statistics kernel: rows in flight x workgroups x load kind
+    for n in (4096, 14336):
+        X = synth.device_activations(T, n, seed=1, device=dev, dtype=storage)
+        settings = [None] + [f"{r},{g}{p}" for p in ("", ",plain") for r in (4, 8, 16) for g in (192, 224, 256, 384, 512, 1024)
+                             if not (p and g not in (224, 256, 384))] + [None]
+        warm = sp.LayerBuffers(8, n, T, dev)
+        for _ in range(40):                                   # clocks and address translation settle first
+            sp.swiftprune_layer_stats(X, warm.xsq, warm.S, warm.hr, workspace=warm.workspace, stream=stream)
+        torch.cuda.synchronize()
+        for st in settings:
+            if st is None:
+                os.environ.pop("SWIFTPRUNE_STATS_PLAN", None)
+            else:
+                os.environ["SWIFTPRUNE_STATS_PLAN"] = st
+            b = sp.LayerBuffers(8, n, T, dev)
+            us = timed(lambda i: sp.swiftprune_layer_stats(X, b.xsq, b.S, b.hr, workspace=b.workspace, stream=stream), reps)
+            say("layer_stats", f"{T}x{n}", st or "built-in", us, T * n * 2)
+        os.environ.pop("SWIFTPRUNE_STATS_PLAN", None)
+        del X
+        torch.cuda.empty_cache()
+    # ---- per-weight kernels: rotating matrices so that no launch re-reads a cached one
+    for out, n in ((1024, 4096), (4096, 4096), (14336, 4096), (4096, 14336)):
+        nbuf = max(2, min(24, (3 << 30) // (out * n * 2)))
+        Ws = [synth.device_weights(out, n, seed=50 + i, device=dev, dtype=storage) for i in range(nbuf)]
+        b = sp.LayerBuffers(out, n, 8, dev)
+        hr = torch.full((n,), 0.5, dtype=torch.float32, device=dev)
+        algo = out * n * 4.125
+        for team in (None, "1", "2", "4"):
+            if team is None:
+                os.environ.pop("SWIFTPRUNE_SELECT_TEAM", None)
+            else:
+                os.environ["SWIFTPRUNE_SELECT_TEAM"] = team
+            us = timed(lambda i: sp.swiftprune_score_select(Ws[i % nbuf], hr, b.keep_mask, la=0.5, row_pruned=b.row_pruned,
+                                                            flags=sp.SP_APPLY_INPLACE, stream=stream), 2 * nbuf)
+            say("score_select+apply", f"{out}x{n}", f"team {team or 'built-in'}", us, algo)
+        os.environ.pop("SWIFTPRUNE_SELECT_TEAM", None)
+        for g in (None, 256, 384, 512, 768, 1024, 2048):
+            if g is None:
+                os.environ.pop("SWIFTPRUNE_BAND_GROUPS", None)
+            else:
+                os.environ["SWIFTPRUNE_BAND_GROUPS"] = f"{g},{g}"
+            us = timed(lambda i: sp.swiftprune_nm_select(Ws[i % nbuf], hr, 2, 4, b.keep_mask, flags=sp.SP_APPLY_INPLACE,
+                                                         stream=stream), 2 * nbuf)
+            say("nm_select 2:4+apply", f"{out}x{n}", f"groups {g or 'built-in'}", us, algo)
+            us = timed(lambda i: sp.swiftprune_apply(Ws[i % nbuf], b.keep_mask, stream=stream), 2 * nbuf)
+            say("apply", f"{out}x{n}", f"groups {g or 'built-in'}", us, algo)
+        os.environ.pop("SWIFTPRUNE_BAND_GROUPS", None)
+        del Ws
+        torch.cuda.empty_cache()
 
 
 def sample_70b(sp, synth, torch, dev, stream, T, storage, blocks, steps):

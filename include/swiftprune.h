@@ -306,6 +306,18 @@ int swiftprune_ewma_trace(const void *W, int64_t out, int64_t in, int64_t ldw, s
                           const float *hr, float alpha, float beta, float *est, float *dev,
                           void *hip_stream);
 
+/*
+ * Launch-shape overrides for measurements.  The kernels' launch shapes (rows in flight and workgroups of
+ * the statistics kernel, wavefronts per row of the EWMA kernel, workgroups of the N:M / apply kernels) were
+ * chosen from sweeps on MI355X.  Three environment variables, read at every call, replace them so that the
+ * sweeps can be repeated; they change how the work is cut, never the results.  Malformed values are ignored.
+ *   SWIFTPRUNE_STATS_PLAN  = "<rows in flight: 4|8|16>,<workgroups 1..4096>[,plain]"
+ *                            (plain = ordinary instead of non-temporal loads, bf16 vector path only;
+ *                            swiftprune_stats_workspace_bytes follows the override)
+ *   SWIFTPRUNE_SELECT_TEAM = "1" | "2" | "4"
+ *   SWIFTPRUNE_BAND_GROUPS = "<apply workgroups>,<N:M select workgroups>" (1..4096 each)
+ */
+
 /* ---- host helpers (no device work) ---- */
 
 /* uint32 words of meta per row for swiftprune_compact_nm (0 on an unsupported pattern). */

@@ -5,6 +5,38 @@
 #include "kernels.hpp"
 
 #include <math.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+namespace sp {
+
+Tuning read_tuning() {
+    Tuning t = {0, 0, false, 0, 0, 0};
+    if (const char* e = getenv("SWIFTPRUNE_STATS_PLAN")) {
+        int rows = 0, groups = 0;
+        if (sscanf(e, "%d,%d", &rows, &groups) == 2 && (rows == 4 || rows == 8 || rows == 16) && groups >= 1 &&
+            groups <= 4096) {
+            t.stats_rows = rows;
+            t.stats_groups = groups;
+            t.stats_plain = strstr(e, ",plain") != nullptr;
+        }
+    }
+    if (const char* e = getenv("SWIFTPRUNE_SELECT_TEAM")) {
+        const int v = atoi(e);
+        if (v == 1 || v == 2 || v == 4) t.team = v;
+    }
+    if (const char* e = getenv("SWIFTPRUNE_BAND_GROUPS")) {
+        int a = 0, b = 0;
+        if (sscanf(e, "%d,%d", &a, &b) == 2 && a >= 1 && a <= 4096 && b >= 1 && b <= 4096) {
+            t.apply_groups = a;
+            t.select_groups = b;
+        }
+    }
+    return t;
+}
+
+}  // namespace sp
 
 namespace {
 

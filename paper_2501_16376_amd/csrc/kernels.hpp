@@ -20,7 +20,21 @@ struct StatsPlan {
     int64_t rows_per_split;  // upper bound of the tokens one workgroup sees
     int combine_groups;      // workgroups of the combine kernel (64 columns each)
     size_t partial_floats;   // splits * units * epu
+    bool plain_loads;        // experiment: ordinary instead of non-temporal loads
 };
+
+// Launch-shape overrides for measurements, read from the environment at every call (unset = the built-in
+// choices, which were swept on MI355X):
+//   SWIFTPRUNE_STATS_PLAN   = "<rows in flight: 4|8|16>,<workgroups>[,plain]"   statistics kernel
+//   SWIFTPRUNE_SELECT_TEAM  = "1" | "2" | "4"                                   wavefronts per row, EWMA kernel
+//   SWIFTPRUNE_BAND_GROUPS  = "<apply>,<N:M select>"                            workgroups of the band kernels
+struct Tuning {
+    int stats_rows, stats_groups;  // 0 = default
+    bool stats_plain;
+    int team;                      // 0 = default
+    int apply_groups, select_groups;
+};
+Tuning read_tuning();
 constexpr size_t kStatsHeaderBytes = 256;  // counters at the start of the workspace
 StatsPlan make_stats_plan(int64_t tokens, int64_t in, int dt, bool vec);
 size_t stats_workspace_bytes(const StatsPlan& p);  // header + per-workgroup S sums + partial rows

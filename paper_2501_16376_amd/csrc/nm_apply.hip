@@ -391,12 +391,14 @@ hipError_t launch_nm_select(const void* W, int64_t out, int64_t in, int64_t ldw,
 hipError_t launch_nm_select_group(const RowGroups& g, int64_t in, int dt, const float* hr, int n_keep,
                                   int m_group, float* scores, bool apply, hipStream_t stream) {
     const int n_prune = m_group - n_keep, ap = apply ? 1 : 0;
+    const Tuning t = read_tuning();
+    const int groups = t.select_groups != 0 ? t.select_groups : kSelectBandGroups;  // measurement override
     return with_dtype(dt, [&](auto tag) {
         constexpr int DT = decltype(tag)::value;
         switch (m_group) {
-            case 4: return launch_nm_band<DT, 4>(g, in, hr, n_prune, scores, ap, kSelectBandGroups, stream);
-            case 8: return launch_nm_band<DT, 8>(g, in, hr, n_prune, scores, ap, kSelectBandGroups, stream);
-            case 16: return launch_nm_band<DT, 16>(g, in, hr, n_prune, scores, ap, kSelectBandGroups, stream);
+            case 4: return launch_nm_band<DT, 4>(g, in, hr, n_prune, scores, ap, groups, stream);
+            case 8: return launch_nm_band<DT, 8>(g, in, hr, n_prune, scores, ap, groups, stream);
+            case 16: return launch_nm_band<DT, 16>(g, in, hr, n_prune, scores, ap, groups, stream);
             default: return hipErrorInvalidValue;
         }
     });
@@ -412,7 +414,10 @@ hipError_t launch_apply(void* W, int64_t out, int64_t in, int64_t ldw, int dt, b
     dim3 grid((unsigned)groups);
     return with_dtype(dt, [&](auto tag) {
         constexpr int DT = decltype(tag)::value;
-        if (vec) return launch_apply_band<DT>(W, out, in, ldw, keep_mask, kApplyBandGroups, stream);
+        if (vec) {
+            const Tuning t = read_tuning();  // measurement override
+            return launch_apply_band<DT>(W, out, in, ldw, keep_mask, t.apply_groups != 0 ? t.apply_groups : kApplyBandGroups, stream);
+        }
         hipLaunchKernelGGL((apply_kernel<DT, false>), grid, dim3(kColThreads), 0, stream, W, out, in, ldw, keep_mask, col_tiles);
         return hipGetLastError();
     });

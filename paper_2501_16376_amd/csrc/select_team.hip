@@ -289,6 +289,7 @@ hipError_t launch_ewma_team(const RowGroups& g, int64_t in, int dt, const float*
                             bool apply, int team, hipStream_t stream) {
     // at least four wavefronts per SIMD (1024 SIMDs) before a row gets a wavefront to itself
     const int64_t out = g.total();
+    if (team == 0) team = read_tuning().team;  // measurement override
     if (team == 0) team = out <= 1024 ? 4 : (out <= 2048 ? 2 : 1);
     return with_dtype(dt, [&](auto tag) {
         constexpr int DT = decltype(tag)::value;

@@ -39,6 +39,9 @@ struct XUnit<kBF16, 8> {
     __device__ __forceinline__ void load(const void* X, int64_t elem) {
         r = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(X) + elem));
     }
+    __device__ __forceinline__ void load_plain(const void* X, int64_t elem) {
+        r = *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(X) + elem);
+    }
     __device__ __forceinline__ void sq_add(float* a) const {
         float v;
         v = bf16lo(r.x); a[0] = fmaf(v, v, a[0]);
@@ -130,7 +133,7 @@ __device__ __forceinline__ double block_sum_256(double v, double* lds4) {
 // partials[split * in_pad + u*EPU + k] = sum over those rows of X[t, u*EPU + k]^2
 // for the units u of its strip (in_pad = units * EPU);
 // group_sums[strip * splits + split] = fp64 sum of that partial row segment (its share of S).
-template <int DT, int EPU, int UNROLL>
+template <int DT, int EPU, int UNROLL, bool PLAIN = false>
 __global__ __launch_bounds__(kStatsThreads) __attribute__((amdgpu_waves_per_eu(1, 2))) void stats_partial_kernel(
     const void* __restrict__ X, int64_t tokens, int64_t units, int strip_units, int64_t ldx,
     float* __restrict__ partials, double* __restrict__ group_sums) {
@@ -172,7 +175,10 @@ __global__ __launch_bounds__(kStatsThreads) __attribute__((amdgpu_waves_per_eu(1
         for (; r + UNROLL <= tokens; r += step) {
             XUnit<DT, EPU> v[UNROLL];
 #pragma unroll
-            for (int j = 0; j < UNROLL; ++j) v[j].load(X, (r + j) * ldx + col);
+            for (int j = 0; j < UNROLL; ++j) {
+                if constexpr (PLAIN) v[j].load_plain(X, (r + j) * ldx + col);   // measurement variant, bf16 vector path only
+                else v[j].load(X, (r + j) * ldx + col);
+            }
             if (++since_fold == kFoldEvery) {  // uniform; runs while the loads above are in flight
                 fold();
                 since_fold = 0;
@@ -326,6 +332,18 @@ StatsPlan make_stats_plan(int64_t tokens, int64_t in, int dt, bool vec) {
     if (splits < 1) splits = 1;
     p.splits = (int)splits;
     p.rows_per_split = ceil_div(batches, splits) * p.unroll;  // upper bound, informational
+    p.plain_loads = false;
+    const Tuning t = read_tuning();
+    if (t.stats_rows != 0) {  // measurement override
+        p.unroll = t.stats_rows;
+        int64_t s2 = t.stats_groups / p.nstrips;
+        const int64_t b2 = ceil_div(tokens, p.unroll);
+        if (s2 > b2) s2 = b2;
+        if (s2 < 1) s2 = 1;
+        p.splits = (int)s2;
+        p.rows_per_split = ceil_div(b2, s2) * p.unroll;
+        p.plain_loads = t.stats_plain && vec && dt == kBF16;
+    }
     p.combine_groups = (int)ceil_div(in, 64);
     p.partial_floats = (size_t)p.splits * (size_t)(p.units * p.epu);
     return p;
@@ -343,6 +361,20 @@ template <int DT, int EPU>
 static hipError_t launch_partial(const void* X, int64_t tokens, int64_t ldx, const StatsPlan& p,
                                  float* partials, double* group_sums, hipStream_t stream) {
     dim3 grid((unsigned)p.nstrips, (unsigned)p.splits);
+    if constexpr (DT == kBF16 && EPU == 8) {
+        if (p.plain_loads) {
+            if (p.unroll == 16)
+                hipLaunchKernelGGL((stats_partial_kernel<DT, EPU, 16, true>), grid, dim3(kStatsThreads), 0, stream, X, tokens,
+                                   p.units, p.strip_units, ldx, partials, group_sums);
+            else if (p.unroll == 4)
+                hipLaunchKernelGGL((stats_partial_kernel<DT, EPU, 4, true>), grid, dim3(kStatsThreads), 0, stream, X, tokens,
+                                   p.units, p.strip_units, ldx, partials, group_sums);
+            else
+                hipLaunchKernelGGL((stats_partial_kernel<DT, EPU, 8, true>), grid, dim3(kStatsThreads), 0, stream, X, tokens,
+                                   p.units, p.strip_units, ldx, partials, group_sums);
+            return hipGetLastError();
+        }
+    }
     if (p.unroll == 16)
         hipLaunchKernelGGL((stats_partial_kernel<DT, EPU, 16>), grid, dim3(kStatsThreads), 0, stream, X, tokens,
                            p.units, p.strip_units, ldx, partials, group_sums);

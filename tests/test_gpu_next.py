@@ -440,3 +440,43 @@ def test_group_selection_matches_per_matrix_oracle(orc, gpu, outs, n, dtype, pad
     if pad:
         for W in Ws:
             assert np.all(synth.torch_to_host_bits(W._base)[:, n:] == 0)
+
+
+def test_launch_shape_overrides_keep_results(orc, gpu, monkeypatch):
+    """The environment overrides used for launch-shape measurements change how the work is cut, never what
+    is computed: statistics, EWMA masks and N:M masks under odd settings still meet the oracle."""
+    import torch
+    from paper_2501_16376_amd import binding as b, synth
+    from gpu_util import to_device, check_ewma_mask, mask_to_host, same_bits
+    out, n, tokens = 300, 2056, 3000
+    Wh, Xh = synth.layer_inputs(out, n, tokens, seed=77, dtype="bf16")
+    xsq_o, S_o, hr_o = orc.layer_stats(Xh)
+    X, hr_dev = to_device(Xh, gpu), to_device(hr_o, gpu)
+    for plan in ("16,384,plain", "4,7", "8,4096"):
+        monkeypatch.setenv("SWIFTPRUNE_STATS_PLAN", plan)
+        buf = b.LayerBuffers(out, n, tokens, gpu)              # sized for the overridden plan
+        b.swiftprune_layer_stats(X, buf.xsq, buf.S, buf.hr, workspace=buf.workspace)
+        torch.cuda.synchronize()
+        assert np.allclose(buf.xsq.cpu().numpy(), xsq_o, rtol=1e-5, atol=0), plan
+        assert np.allclose(buf.hr.cpu().numpy(), hr_o, rtol=1e-5, atol=0), plan
+    monkeypatch.setenv("SWIFTPRUNE_STATS_PLAN", "nonsense")   # ignored
+    b.swiftprune_layer_stats(X, buf.xsq, buf.S, buf.hr)
+    torch.cuda.synchronize()
+    assert np.allclose(buf.xsq.cpu().numpy(), xsq_o, rtol=1e-5, atol=0)
+    monkeypatch.delenv("SWIFTPRUNE_STATS_PLAN")
+    nm_o, _ = orc.nm_select(Wh, hr_o, 2, 4)
+    for team, groups in (("1", "3,5"), ("2", "4096,4096"), ("4", "64,64")):
+        monkeypatch.setenv("SWIFTPRUNE_SELECT_TEAM", team)
+        monkeypatch.setenv("SWIFTPRUNE_BAND_GROUPS", groups)
+        W = to_device(Wh, gpu)
+        b.swiftprune_score_select(W, hr_dev, buf.keep_mask, la=0.5, row_pruned=buf.row_pruned, flags=b.SP_APPLY_INPLACE)
+        torch.cuda.synchronize()
+        m = mask_to_host(buf.keep_mask)
+        check_ewma_mask(orc, Wh, hr_o, A, B, 0.5, m, buf.row_pruned.cpu().numpy())
+        assert same_bits(synth.torch_to_host_bits(W), orc.apply(Wh.copy(), m))
+        W = to_device(Wh, gpu)
+        b.swiftprune_nm_select(W, hr_dev, 2, 4, buf.keep_mask)
+        b.swiftprune_apply(W, buf.keep_mask)
+        torch.cuda.synchronize()
+        assert np.array_equal(mask_to_host(buf.keep_mask), nm_o)
+        assert same_bits(synth.torch_to_host_bits(W), orc.apply(Wh.copy(), nm_o))
