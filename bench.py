@@ -344,6 +344,7 @@ def main():
         else:
             secondary.append(side_entry(stack, stream, k, f"{name}, unstructured (la={la:g})", la=la))
         result["secondary"] = secondary
+        result["chunked_stats"] = chunked_stats(sp, torch, stack, stream)
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -435,6 +436,40 @@ def tuning_sweep(sp, synth, torch, dev, T, storage, reps=6):
         os.environ.pop("SWIFTPRUNE_BAND_GROUPS", None)
         del Ws
         torch.cuda.empty_cache()
+
+
+def chunked_stats(sp, torch, stack, stream, chunks=8, reps=10):
+    """Statistics of one layer input arriving in token chunks (as a producer of X would hand them over):
+    `chunks` accumulate calls, the last one finalising, against the single call on the whole X."""
+    key, n = next(iter(sorted(stack.widths.items())))
+    X, T = stack.X[key], stack.T
+    b = stack.bufs[0] if stack.block[0][2] == n else sp.LayerBuffers(8, n, T, stack.dev)
+    per = T // chunks
+
+    def chunked():
+        for c in range(chunks):
+            sp.swiftprune_layer_stats(X[c * per:(c + 1) * per if c < chunks - 1 else T], b.xsq, b.S, b.hr,
+                                      accumulate=c > 0, finalize=c == chunks - 1, workspace=b.workspace, stream=stream)
+
+    def whole():
+        sp.swiftprune_layer_stats(X, b.xsq, b.S, b.hr, workspace=b.workspace, stream=stream)
+
+    out = {}
+    for name, fn in (("whole", whole), ("chunked", chunked)):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            fn()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        out[name] = e0.elapsed_time(e1) / reps * 1e3
+    nbytes = T * n * 2
+    return {"workload": f"statistics of one {T} x {n} layer input in {chunks} token chunks (accumulate mode)",
+            "chunks": chunks, "us_chunked": round(out["chunked"], 1), "us_single_call": round(out["whole"], 1),
+            "hbm_frac_chunked": round(nbytes / out["chunked"] / 1e6 / HBM_PEAK_GBS, 4),
+            "hbm_frac_single_call": round(nbytes / out["whole"] / 1e6 / HBM_PEAK_GBS, 4)}
 
 
 def sample_70b(sp, synth, torch, dev, stream, T, storage, blocks, steps):

@@ -63,8 +63,8 @@ struct EwmaConsts {
     float thr_scale;    // (1-alpha) * la * beta: prune iff alpha*x_k - L_k > thr_scale * y_{k-1}
     float A_pow[9];     // (1-alpha)^k, k = 0..8
     float B_pow[9];     // (1-beta)^k
-    double A8_sq[7];    // ((1-alpha)^8)^(2^i), i = 0..6
-    double B8_sq[7];
+    float A8_pow[65];   // ((1-alpha)^8)^k, k = 0..64: the weight of a state k lanes (8 k columns) to the left
+    float B8_pow[65];
     const float* la_dev;  // nullable: when set, la is read from device memory by the kernel (la, thr_scale unused)
 };
 EwmaConsts make_ewma_consts(float alpha, float beta, float la);

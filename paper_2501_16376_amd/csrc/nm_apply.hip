@@ -2,13 +2,15 @@
 // in-place apply step (Algorithm 1: pruned w_i = 0).
 //
 // Both are plain streaming kernels.  A lane owns one chunk of 8 consecutive
-// columns (one 16-byte load of bf16) and walks kRows rows with it, so the
-// channel factors of its columns are loaded once and kRows independent loads
+// columns (one 16-byte load of bf16) and walks several rows with it, so the
+// channel factors of its columns are loaded once and several independent loads
 // are in flight.  N:M ranks are computed in registers by counting, with ties
 // broken towards the lower index: rank_i = #{p : (L_p, p) < (L_i, i)}, and
 // entry i is pruned iff rank_i < M - N.  Groups of 4 and 8 live inside one
 // lane; a group of 16 spans two neighbouring lanes and exchanges its scores
 // with one DPP quad permute per value.
+// Two kernel families: tile kernels for element-wise layouts (odd widths,
+// unaligned pointers), band kernels for the 16-byte-vector layout.
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -71,7 +73,7 @@ __device__ __forceinline__ uint32_t nm_keep_bits16(const float* L, int n_prune, 
 // A wavefront owns a tile of kRows rows x 64 chunks (512 columns); tiles are numbered column-first, so the
 // four wavefronts of a workgroup and consecutive workgroups touch consecutive memory, and a row width that
 // is not a multiple of 2048 columns wastes at most part of one wavefront.  grid = ceil(tiles / 4), block = 256.
-template <int DT, bool VEC, int M>
+template <int DT, int M>
 __global__ __launch_bounds__(kColThreads) void nm_select_kernel(
     void* __restrict__ W, int64_t out, int64_t in, int64_t ldw, const float* __restrict__ hr,
     int n_prune, uint32_t* __restrict__ keep_mask, float* __restrict__ scores, int apply,
@@ -86,16 +88,14 @@ __global__ __launch_bounds__(kColThreads) void nm_select_kernel(
     const int nrows = (int)max((int64_t)0, min((int64_t)kRows, out - row0));  // 0 for a wavefront past the last tile
 
     Factor8 f;
-    if (VEC) { if (valid) f.load_vec(hr, q0); else f.load_elems(hr, q0, 0); }
-    else f.load_elems(hr, q0, valid);
+    f.load_elems(hr, q0, valid);
 
     Chunk8<DT> w[kRows];
 #pragma unroll
     for (int r = 0; r < kRows; ++r) {
         w[r].zero();
         if (r < nrows && valid) {
-            if (VEC) w[r].load_vec(W, (row0 + r) * ldw + q0);
-            else w[r].load_elems(W, (row0 + r) * ldw + q0, valid);
+            w[r].load_elems(W, (row0 + r) * ldw + q0, valid);
         }
     }
 #pragma unroll
@@ -107,20 +107,19 @@ __global__ __launch_bounds__(kColThreads) void nm_select_kernel(
         uint32_t keep = (M == 16) ? nm_keep_bits16(L, n_prune, lane) : nm_keep_bits<(M == 16 ? 8 : M)>(L, n_prune);
         keep &= (valid >= 8) ? 0xffu : ((1u << valid) - 1u);
         const int64_t row = row0 + r;
-        if (scores != nullptr && valid) store8(scores + row * in + q0, L, VEC, valid);
+        if (scores != nullptr && valid) store8(scores + row * in + q0, L, false, valid);
         const uint32_t word = quad_gather_bytes(keep, lane);
         const int64_t widx = q0 >> 5;
         if ((lane & 3) == 0 && widx < mask_words) keep_mask[row * mask_words + widx] = word;
         if (apply && valid) {
             w[r].apply(keep);
-            if (VEC) w[r].store_vec_nt(W, row * ldw + q0);
-            else w[r].store_elems(W, row * ldw + q0, valid);
+            w[r].store_elems(W, row * ldw + q0, valid);
         }
     }
 }
 
 // grid / block as above
-template <int DT, bool VEC>
+template <int DT>
 __global__ __launch_bounds__(kColThreads) void apply_kernel(void* __restrict__ W, int64_t out, int64_t in,
                                                            int64_t ldw,
                                                            const uint32_t* __restrict__ keep_mask,
@@ -140,8 +139,7 @@ __global__ __launch_bounds__(kColThreads) void apply_kernel(void* __restrict__ W
 #pragma unroll
     for (int r = 0; r < kRows; ++r) {
         if (r < nrows) {
-            if (VEC) w[r].load_vec(W, (row0 + r) * ldw + q0);
-            else w[r].load_elems(W, (row0 + r) * ldw + q0, valid);
+            w[r].load_elems(W, (row0 + r) * ldw + q0, valid);
             keep[r] = (keep_mask[(row0 + r) * mask_words + (q0 >> 5)] >> shift) & 0xffu;
         }
     }
@@ -149,8 +147,7 @@ __global__ __launch_bounds__(kColThreads) void apply_kernel(void* __restrict__ W
     for (int r = 0; r < kRows; ++r) {
         if (r < nrows) {
             w[r].apply(keep[r]);
-            if (VEC) w[r].store_vec_nt(W, (row0 + r) * ldw + q0);
-            else w[r].store_elems(W, (row0 + r) * ldw + q0, valid);
+            w[r].store_elems(W, (row0 + r) * ldw + q0, valid);
         }
     }
 }
@@ -344,7 +341,7 @@ static hipError_t launch_apply_band(void* W, int64_t out, int64_t in, int64_t ld
     return hipGetLastError();
 }
 
-template <int DT, bool VEC>
+template <int DT>
 static hipError_t launch_nm_t(const void* W, int64_t out, int64_t in, int64_t ldw, const float* hr,
                               int n_keep, int m_group, uint32_t* keep_mask, float* scores, bool apply,
                               hipStream_t stream) {
@@ -359,15 +356,15 @@ static hipError_t launch_nm_t(const void* W, int64_t out, int64_t in, int64_t ld
     const int ap = apply ? 1 : 0;
     switch (m_group) {
         case 4:
-            hipLaunchKernelGGL((nm_select_kernel<DT, VEC, 4>), grid, dim3(kColThreads), 0, stream, Wm, out, in,
+            hipLaunchKernelGGL((nm_select_kernel<DT, 4>), grid, dim3(kColThreads), 0, stream, Wm, out, in,
                                ldw, hr, n_prune, keep_mask, scores, ap, col_tiles);
             break;
         case 8:
-            hipLaunchKernelGGL((nm_select_kernel<DT, VEC, 8>), grid, dim3(kColThreads), 0, stream, Wm, out, in,
+            hipLaunchKernelGGL((nm_select_kernel<DT, 8>), grid, dim3(kColThreads), 0, stream, Wm, out, in,
                                ldw, hr, n_prune, keep_mask, scores, ap, col_tiles);
             break;
         case 16:
-            hipLaunchKernelGGL((nm_select_kernel<DT, VEC, 16>), grid, dim3(kColThreads), 0, stream, Wm, out, in,
+            hipLaunchKernelGGL((nm_select_kernel<DT, 16>), grid, dim3(kColThreads), 0, stream, Wm, out, in,
                                ldw, hr, n_prune, keep_mask, scores, ap, col_tiles);
             break;
         default:
@@ -384,7 +381,7 @@ hipError_t launch_nm_select(const void* W, int64_t out, int64_t in, int64_t ldw,
         if (vec)
             return launch_nm_select_group(single_matrix(W, out, ldw, keep_mask, nullptr), in, DT, hr, n_keep, m_group,
                                           scores, apply, stream);
-        return launch_nm_t<DT, false>(W, out, in, ldw, hr, n_keep, m_group, keep_mask, scores, apply, stream);
+        return launch_nm_t<DT>(W, out, in, ldw, hr, n_keep, m_group, keep_mask, scores, apply, stream);
     });
 }
 
@@ -418,7 +415,7 @@ hipError_t launch_apply(void* W, int64_t out, int64_t in, int64_t ldw, int dt, b
             const Tuning t = read_tuning();  // measurement override
             return launch_apply_band<DT>(W, out, in, ldw, keep_mask, t.apply_groups != 0 ? t.apply_groups : kApplyBandGroups, stream);
         }
-        hipLaunchKernelGGL((apply_kernel<DT, false>), grid, dim3(kColThreads), 0, stream, W, out, in, ldw, keep_mask, col_tiles);
+        hipLaunchKernelGGL((apply_kernel<DT>), grid, dim3(kColThreads), 0, stream, W, out, in, ldw, keep_mask, col_tiles);
         return hipGetLastError();
     });
 }

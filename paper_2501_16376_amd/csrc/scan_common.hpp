@@ -41,23 +41,17 @@ struct ScanLaneConsts {
     float m1, m2, m4, m8;  // m^1, m^2, m^4, m^8 (uniform)
 };
 
-__device__ __forceinline__ float pow_bits(const double* sq, int e) {
-    double p = 1.0;
-#pragma unroll
-    for (int i = 0; i < 7; ++i)
-        if ((e >> i) & 1) p *= sq[i];
-    return (float)p;
-}
-
-__device__ __forceinline__ ScanLaneConsts make_lane_consts(const double* sq, int lane) {
+// per-lane scan weights from the host's table pw[k] = m^k, k = 0..64 (m = A^8 or B^8), each rounded once
+// from double
+__device__ __forceinline__ ScanLaneConsts make_lane_consts(const float* pw, int lane) {
     ScanLaneConsts c;
-    c.shift = pow_bits(sq, lane);
-    c.cross15 = pow_bits(sq, (lane & 15) + 1);
-    c.cross31 = pow_bits(sq, (lane & 31) + 1);
-    c.m1 = (float)sq[0];
-    c.m2 = (float)sq[1];
-    c.m4 = (float)sq[2];
-    c.m8 = (float)sq[3];
+    c.shift = pw[lane];
+    c.cross15 = pw[(lane & 15) + 1];
+    c.cross31 = pw[(lane & 31) + 1];
+    c.m1 = pw[1];
+    c.m2 = pw[2];
+    c.m4 = pw[4];
+    c.m8 = pw[8];
     return c;
 }
 
@@ -84,8 +78,8 @@ template <int DT, bool VEC, class Body>
 __device__ __forceinline__ void ewma_walk_row(const void* W, int64_t row, int64_t in, int64_t ldw,
                                               const float* __restrict__ hr, const EwmaConsts& c, int lane,
                                               float* __restrict__ scores, Body&& body) {
-    const ScanLaneConsts ce = make_lane_consts(c.A8_sq, lane);
-    const ScanLaneConsts cd = make_lane_consts(c.B8_sq, lane);
+    const ScanLaneConsts ce = make_lane_consts(c.A8_pow, lane);
+    const ScanLaneConsts cd = make_lane_consts(c.B8_pow, lane);
     const int64_t nseg = (in + 511) >> 9;
     float carry_e = 0.f, carry_d = 0.f;
 

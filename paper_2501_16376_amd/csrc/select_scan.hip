@@ -75,12 +75,13 @@ EwmaConsts make_ewma_consts(float alpha, float beta, float la) {
         c.A_pow[k] = (float)pow(A, k);
         c.B_pow[k] = (float)pow(B, k);
     }
-    double a = pow(A, 8), b = pow(B, 8);
-    for (int i = 0; i < 7; ++i) {
-        c.A8_sq[i] = a;
-        c.B8_sq[i] = b;
-        a *= a;
-        b *= b;
+    const double a = pow(A, 8), b = pow(B, 8);
+    double ak = 1.0, bk = 1.0;  // running products in double: 64 roundings of 2^-53 each, far below fp32's
+    for (int k = 0; k <= 64; ++k) {
+        c.A8_pow[k] = (float)ak;
+        c.B8_pow[k] = (float)bk;
+        ak *= a;
+        bk *= b;
     }
     return c;
 }

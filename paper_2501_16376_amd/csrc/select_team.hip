@@ -101,11 +101,11 @@ __global__ __launch_bounds__(kTeamThreads) void ewma_team_kernel(
     const int64_t span_cols = (int64_t)NW * kSegs * 512;
     const int64_t nspans = (in + span_cols - 1) / span_cols;
 
-    const ScanLaneConsts ce = make_lane_consts(c.A8_sq, lane);
-    const ScanLaneConsts cd = make_lane_consts(c.B8_sq, lane);
+    const ScanLaneConsts ce = make_lane_consts(c.A8_pow, lane);
+    const ScanLaneConsts cd = make_lane_consts(c.B8_pow, lane);
     const float A = c.A_pow[1], B = c.B_pow[1];
     const float thr_scale = ewma_thr_scale(c);
-    const float A512 = (float)c.A8_sq[6], B512 = (float)c.B8_sq[6];
+    const float A512 = c.A8_pow[64], B512 = c.B8_pow[64];
     // entry weight of a run's s-th segment at this lane, and of a whole run
     float shift_x[kSegs], shift_y[kSegs];
     shift_x[0] = ce.shift;
