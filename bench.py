@@ -468,8 +468,8 @@ def chunked_stats(sp, torch, stack, stream, chunks=8, reps=10):
     nbytes = T * n * 2
     return {"workload": f"statistics of one {T} x {n} layer input in {chunks} token chunks (accumulate mode)",
             "chunks": chunks, "us_chunked": round(out["chunked"], 1), "us_single_call": round(out["whole"], 1),
-            "hbm_frac_chunked": round(nbytes / out["chunked"] / 1e6 / HBM_PEAK_GBS, 4),
-            "hbm_frac_single_call": round(nbytes / out["whole"] / 1e6 / HBM_PEAK_GBS, 4)}
+            "hbm_frac_chunked": round(nbytes / out["chunked"] / 1e3 / HBM_PEAK_GBS, 4),
+            "hbm_frac_single_call": round(nbytes / out["whole"] / 1e3 / HBM_PEAK_GBS, 4)}
 
 
 def sample_70b(sp, synth, torch, dev, stream, T, storage, blocks, steps):
