@@ -179,7 +179,7 @@ BandPlan make_band_plan(int64_t out, int64_t in, int target_groups, int unroll =
     nstrips = (units + su - 1) / su;
     p.strip_units = (int)su;
     p.nstrips = (int)nstrips;
-    p.unroll = unroll;
+    p.unroll = unroll > 4 ? 4 : unroll;  // 1, 2 or 4 rows per batch
     int64_t splits = target_groups / nstrips;
     // small matrices: fewer rows per batch before fewer workgroups
     while (p.unroll > 1 && (out + p.unroll - 1) / p.unroll < splits) p.unroll >>= 1;
@@ -312,7 +312,6 @@ static hipError_t launch_nm_band_t(const RowGroups& g, int64_t in, const float* 
     const BandPlan p = make_band_plan(g.total(), in, target_groups, unroll);
     const dim3 grid((unsigned)p.nstrips, (unsigned)p.splits), block(kColThreads);
     switch (p.unroll) {
-        case 8: hipLaunchKernelGGL((nm_select_band_kernel<DT, M, 8, GROUPED>), grid, block, 0, stream, g, in, hr, n_prune, scores, apply, p.strip_units); break;
         case 4: hipLaunchKernelGGL((nm_select_band_kernel<DT, M, 4, GROUPED>), grid, block, 0, stream, g, in, hr, n_prune, scores, apply, p.strip_units); break;
         case 2: hipLaunchKernelGGL((nm_select_band_kernel<DT, M, 2, GROUPED>), grid, block, 0, stream, g, in, hr, n_prune, scores, apply, p.strip_units); break;
         default: hipLaunchKernelGGL((nm_select_band_kernel<DT, M, 1, GROUPED>), grid, block, 0, stream, g, in, hr, n_prune, scores, apply, p.strip_units); break;
@@ -333,7 +332,6 @@ static hipError_t launch_apply_band(void* W, int64_t out, int64_t in, int64_t ld
     const BandPlan p = make_band_plan(out, in, target_groups, unroll);
     const dim3 grid((unsigned)p.nstrips, (unsigned)p.splits), block(kColThreads);
     switch (p.unroll) {
-        case 8: hipLaunchKernelGGL((apply_band_kernel<DT, 8>), grid, block, 0, stream, W, out, in, ldw, keep_mask, p.strip_units); break;
         case 4: hipLaunchKernelGGL((apply_band_kernel<DT, 4>), grid, block, 0, stream, W, out, in, ldw, keep_mask, p.strip_units); break;
         case 2: hipLaunchKernelGGL((apply_band_kernel<DT, 2>), grid, block, 0, stream, W, out, in, ldw, keep_mask, p.strip_units); break;
         default: hipLaunchKernelGGL((apply_band_kernel<DT, 1>), grid, block, 0, stream, W, out, in, ldw, keep_mask, p.strip_units); break;
