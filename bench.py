@@ -436,6 +436,32 @@ def tuning_sweep(sp, synth, torch, dev, T, storage, reps=6):
         os.environ.pop("SWIFTPRUNE_BAND_GROUPS", None)
         del Ws
         torch.cuda.empty_cache()
+    # ---- time against the number of rows at one width: the slope is the streaming rate of the kernel, the
+    # intercept what a launch costs before and after it streams (start-up, per-wavefront set-up, drain)
+    n = 4096
+    arena = synth.device_weights(3 * 24576, n, seed=77, device=dev, dtype=storage)     # 604 MB, three windows of the largest
+    hr = torch.full((n,), 0.5, dtype=torch.float32, device=dev)
+    b = sp.LayerBuffers(24576, n, 8, dev)
+    calls = {
+        "score_select+apply": lambda W: sp.swiftprune_score_select(W, hr, b.keep_mask, la=0.5, row_pruned=b.row_pruned,
+                                                                   flags=sp.SP_APPLY_INPLACE, stream=stream),
+        "nm_select 2:4+apply": lambda W: sp.swiftprune_nm_select(W, hr, 2, 4, b.keep_mask, flags=sp.SP_APPLY_INPLACE,
+                                                                 stream=stream),
+        "apply": lambda W: sp.swiftprune_apply(W, b.keep_mask, stream=stream),
+    }
+    for kind, call in calls.items():
+        pts = []
+        for out in (4096, 6144, 8192, 10240, 12288, 14336, 16384, 20480, 24576):
+            nwin = arena.shape[0] // out
+            us = timed(lambda i: call(arena[(i % nwin) * out:(i % nwin + 1) * out]), 24)
+            say(kind, f"{out}x{n}", "rows sweep", us, out * n * 4.125)
+            pts.append((out, us))
+        mx = sum(p[0] for p in pts) / len(pts)
+        my = sum(p[1] for p in pts) / len(pts)
+        slope = sum((p[0] - mx) * (p[1] - my) for p in pts) / sum((p[0] - mx) ** 2 for p in pts)
+        print(json.dumps({"kernel": kind, "width": n, "fit": "us = intercept + slope * rows / 1024",
+                          "slope_us_per_1024_rows": round(slope * 1024, 3), "intercept_us": round(my - slope * mx, 2),
+                          "streaming_TBps": round(1024 * n * 4.125 / (slope * 1024) / 1e6, 3)}), flush=True)
 
 
 def chunked_stats(sp, torch, stack, stream, chunks=8, reps=10):
