@@ -414,7 +414,7 @@ def tuning_sweep(sp, synth, torch, dev, T, storage, reps=6):
         b = sp.LayerBuffers(out, n, 8, dev)
         hr = torch.full((n,), 0.5, dtype=torch.float32, device=dev)
         algo = out * n * 4.125
-        for team in (None, "1", "2", "4"):
+        for team in (None, "1", "2", "4", "1,direct", "2,direct", "4,direct"):
             if team is None:
                 os.environ.pop("SWIFTPRUNE_SELECT_TEAM", None)
             else:

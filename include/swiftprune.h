@@ -314,7 +314,9 @@ int swiftprune_ewma_trace(const void *W, int64_t out, int64_t in, int64_t ldw, s
  *   SWIFTPRUNE_STATS_PLAN  = "<rows in flight: 4|8|16>,<workgroups 1..4096>[,plain]"
  *                            (plain = ordinary instead of non-temporal loads, bf16 vector path only;
  *                            swiftprune_stats_workspace_bytes follows the override)
- *   SWIFTPRUNE_SELECT_TEAM = "1" | "2" | "4"
+ *   SWIFTPRUNE_SELECT_TEAM = "<0|1|2|4>[,direct]"  (wavefronts per row, 0 = built-in choice; direct = every span
+ *                            loads its weights and channel factors from global memory and waits for them,
+ *                            instead of factors staged in LDS and weights requested one span ahead)
  *   SWIFTPRUNE_BAND_GROUPS = "<apply workgroups>,<N:M select workgroups>" (1..4096 each)
  */
 

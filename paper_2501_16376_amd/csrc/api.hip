@@ -12,7 +12,7 @@
 namespace sp {
 
 Tuning read_tuning() {
-    Tuning t = {0, 0, false, 0, 0, 0};
+    Tuning t = {0, 0, false, 0, false, 0, 0};
     if (const char* e = getenv("SWIFTPRUNE_STATS_PLAN")) {
         int rows = 0, groups = 0;
         if (sscanf(e, "%d,%d", &rows, &groups) == 2 && (rows == 4 || rows == 8 || rows == 16) && groups >= 1 &&
@@ -25,6 +25,7 @@ Tuning read_tuning() {
     if (const char* e = getenv("SWIFTPRUNE_SELECT_TEAM")) {
         const int v = atoi(e);
         if (v == 1 || v == 2 || v == 4) t.team = v;
+        t.select_direct = strstr(e, ",direct") != nullptr;
     }
     if (const char* e = getenv("SWIFTPRUNE_BAND_GROUPS")) {
         int a = 0, b = 0;

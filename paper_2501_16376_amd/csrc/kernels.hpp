@@ -26,12 +26,14 @@ struct StatsPlan {
 // Launch-shape overrides for measurements, read from the environment at every call (unset = the built-in
 // choices, which were swept on MI355X):
 //   SWIFTPRUNE_STATS_PLAN   = "<rows in flight: 4|8|16>,<workgroups>[,plain]"   statistics kernel
-//   SWIFTPRUNE_SELECT_TEAM  = "1" | "2" | "4"                                   wavefronts per row, EWMA kernel
+//   SWIFTPRUNE_SELECT_TEAM  = "<0|1|2|4>[,direct]"                               wavefronts per row, EWMA kernel (0 = built-in);
+//                                                                               direct = no LDS staging, no request ahead
 //   SWIFTPRUNE_BAND_GROUPS  = "<apply>,<N:M select>"                            workgroups of the band kernels
 struct Tuning {
     int stats_rows, stats_groups;  // 0 = default
     bool stats_plain;
     int team;                      // 0 = default
+    bool select_direct;
     int apply_groups, select_groups;
 };
 Tuning read_tuning();

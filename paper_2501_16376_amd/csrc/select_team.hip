@@ -20,7 +20,7 @@
 // per-element values, so the stitching costs no extra work per weight.
 // NW = 4 puts a whole 4096-column row in flight at once (short matrices: four
 // times the wavefronts, a quarter of the serial work per row); NW = 1 is one
-// wavefront per row with no LDS traffic and no barriers (tall matrices).
+// wavefront per row with no exchange between wavefronts (tall matrices).
 //
 // Decisions:  L_q < est_{q-1} - la dev_{q-1}.  The est update gives
 // est_q - L_q = A (est_{q-1} - L_q), hence  prune  <=>  alpha x_q - L_q > (A la beta) y_{q-1}.
@@ -30,10 +30,13 @@
 
 #include <math.h>
 
+#include <type_traits>
+
 namespace sp {
 
 constexpr int kTeamThreads = 256;
 constexpr int kSegs = 2;  // consecutive 512-column segments a wavefront handles per span
+constexpr int64_t kStagedCols = 4096;  // channel factors staged in LDS at a time (16 KB a workgroup)
 
 // Inclusive weighted scans over the 64 lanes of two independent values at once:
 //     r_j = sum_{i <= j} m^(j-i) v_i        (m = c.m1 per lane step)
@@ -64,6 +67,14 @@ __device__ __forceinline__ void team_scan2(float& r0, float& r1, const ScanLaneC
 #undef SP_STEP
 }
 
+// Where the factor of column q (relative to the staged chunk, a multiple of 4) sits in LDS: per 512-column
+// segment first the lanes' factors 0..3, then their factors 4..7.  A lane reads its eight factors with two
+// 16-byte reads; in this layout neighbouring lanes' reads are 16 bytes apart (in column order they would be
+// 32 bytes apart and collide two by two on the LDS banks).
+__device__ __forceinline__ int staged_slot(int q) {
+    return (q & ~511) | ((q & 4) << 6) | (((q & 511) >> 3) << 2);
+}
+
 // workgroup barrier that orders LDS traffic only: outstanding global loads and stores keep flying
 __device__ __forceinline__ void team_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
@@ -73,10 +84,22 @@ __device__ __forceinline__ void team_barrier() {
 
 // grid = ceil(rows of all matrices / (4 / NW)), block = 256 (4 wavefronts).  Requires the 16-byte-vector layout
 // (W and hr 16-byte aligned, in % 8 == 0, ldw a multiple of 16 bytes) and alpha < 1.
-template <int DT, int NW>
+//
+// STAGED (the built-in choice): the channel factors of kStagedCols columns at a time are copied into LDS by the
+// workgroup (dynamic shared memory: kStagedCols floats), and the weights of the next span are requested while
+// the current one is worked on, so that a span starts with nothing to wait for but LDS.  The wavefronts of a
+// launch that fits the device at once move in lock step - all wait for their loads, then all compute - so
+// without this the memory system idles while the vector units work and the other way round.  The other
+// version (each span loads its weights and factors from global memory and waits) is kept for comparison.
+//
+// A span that lies inside the row (FULL) stores without any predicate: every store is then issued on every
+// path, the number of memory operations behind the requested loads is fixed, and the wait for those loads
+// does not have to include the stores that follow them (vmcnt counts loads and stores in one order).
+template <int DT, int NW, bool STAGED, bool APPLY>
 __global__ __launch_bounds__(kTeamThreads) void ewma_team_kernel(
-    const RowGroups g, int64_t in, const float* __restrict__ hr, const EwmaConsts c, int apply) {
+    const RowGroups g, int64_t in, const float* __restrict__ hr, const EwmaConsts c) {
     constexpr int kRowsPerGroup = 4 / NW;
+    extern __shared__ __align__(16) float lds_hr[];
     __shared__ float lds_x[kRowsPerGroup][NW];
     __shared__ float lds_y[kRowsPerGroup][NW];
     __shared__ float lds_first[kRowsPerGroup];
@@ -87,7 +110,7 @@ __global__ __launch_bounds__(kTeamThreads) void ewma_team_kernel(
     const int slot = wave / NW;  // which row of the workgroup
     const int part = wave % NW;  // which run of the row's spans
     const int32_t global_row = (int32_t)(blockIdx.x * kRowsPerGroup + slot);   // the launcher keeps the row total below 2^31
-    const bool has_row = global_row < g.total();
+    const bool has_row = __builtin_amdgcn_readfirstlane((int)(global_row < g.total())) != 0;  // uniform, and known to be
     // a wavefront without a row (past the last one) still walks the loop and meets the barriers, with all
     // its lanes switched off
     const RowOwner<RowGroups> own(g, has_row ? global_row : 0);
@@ -99,7 +122,7 @@ __global__ __launch_bounds__(kTeamThreads) void ewma_team_kernel(
     const int64_t row_off = row * own.ldw;
     const int64_t mask_words = (in + 31) >> 5;
     const int64_t span_cols = (int64_t)NW * kSegs * 512;
-    const int64_t nspans = (in + span_cols - 1) / span_cols;
+    const int nspans = (int)((in + span_cols - 1) / span_cols);  // 32-bit: the scalar unit compares no wider
 
     const ScanLaneConsts ce = make_lane_consts(c.A8_pow, lane);
     const ScanLaneConsts cd = make_lane_consts(c.B8_pow, lane);
@@ -128,9 +151,57 @@ __global__ __launch_bounds__(kTeamThreads) void ewma_team_kernel(
     // lanes past the end of the row (and wavefronts without a row) read valid memory and compute on it, but
     // store nothing: whatever they compute can only reach columns to their right, which do not exist either
     const int64_t row_off_ld = row_off;
+    const int64_t lane_col = (int64_t)part * (kSegs * 512) + (int64_t)lane * 8;
 
-    for (int64_t span = 0; span < nspans; ++span) {
-        const int64_t q_run = span * span_cols + (int64_t)part * (kSegs * 512) + (int64_t)lane * 8;
+    Chunk8<DT> ahead[kSegs];  // STAGED: the weights of the span to come
+    auto request = [&](int span) {
+#pragma unroll
+        for (int s = 0; s < kSegs; ++s) {
+            const int64_t q0 = (int64_t)span * span_cols + lane_col + (int64_t)s * 512;
+            ahead[s].load_vec(W, row_off_ld + (q0 < cols ? q0 : 0));
+        }
+    };
+    // STAGED: kStagedCols factors at a time sit in LDS; a chunk is replaced every kStageSpans spans, by all
+    // wavefronts of the workgroup together (they walk the same columns, of one row or of several)
+    constexpr int kStageSpans = (int)(kStagedCols / ((int64_t)NW * kSegs * 512));
+    auto stage = [&](int span) {
+        if (span != 0) team_barrier();  // nobody reads the chunk before any more
+        const int64_t base = (int64_t)span * span_cols;
+        const int64_t n = in - base < kStagedCols ? in - base : kStagedCols;
+        // all loads first, then all LDS writes: one memory latency per chunk, not one per pass
+        constexpr int kPasses = (int)(kStagedCols / (kTeamThreads * 4));
+        u32x4 v[kPasses];  // a native vector type: an array of HIP's float4 ends up in private memory
+#pragma unroll
+        for (int j = 0; j < kPasses; ++j) {
+            const int64_t q = (int64_t)threadIdx.x * 4 + (int64_t)j * kTeamThreads * 4;
+            v[j] = *reinterpret_cast<const u32x4*>(hr + base + (q < n ? q : 0));
+        }
+#pragma unroll
+        for (int j = 0; j < kPasses; ++j) {
+            const int64_t q = (int64_t)threadIdx.x * 4 + (int64_t)j * kTeamThreads * 4;
+            *reinterpret_cast<u32x4*>(lds_hr + staged_slot((int)q)) = v[j];  // past the row end: a copy of the chunk's start, never read
+        }
+        team_barrier();
+    };
+    if (STAGED) {
+        request(0);
+        stage(0);
+        // The first request is taken as complete here (the copy above has waited for later loads anyway).
+        // Entering the loop with it still pending would make the compiler wait, at the top of every
+        // iteration, as if the newest memory operations were loads to be waited for - and there they are
+        // the stores of the span before.
+#pragma unroll
+        for (int s = 0; s < kSegs; ++s)
+#pragma unroll
+            for (int j = 0; j < (int)(sizeof(ahead[s].raw) / sizeof(ahead[s].raw[0])); ++j)
+                asm volatile("" : "+v"(ahead[s].raw[j]));
+    }
+
+    auto work = [&](int span, auto full_tag) {
+        constexpr bool FULL = decltype(full_tag)::value;
+        const int64_t q_run = (int64_t)span * span_cols + lane_col;
+        const int64_t chunk_base = (int64_t)(span - span % kStageSpans) * span_cols;  // first column of the staged chunk
+        if (STAGED && span != 0 && span % kStageSpans == 0) stage(span);
 
         // ---- scores and the x recurrence of this run, from a zero entry state
         Unpacked8<DT> w[kSegs];
@@ -139,12 +210,22 @@ __global__ __launch_bounds__(kTeamThreads) void ewma_team_kernel(
 #pragma unroll
         for (int s = 0; s < kSegs; ++s) {
             const int64_t q0 = q_run + (int64_t)s * 512;
-            const int64_t q_ld = q0 < cols ? q0 : 0;
-            Chunk8<DT> raw;
-            raw.load_vec(W, row_off_ld + q_ld);
-            f[s].load_vec(hr, q_ld);
-            w[s].unpack(raw);
+            const int64_t q_ld = (FULL || q0 < cols) ? q0 : 0;
+            if (STAGED) {
+                const int slot = staged_slot((FULL || q0 < cols) ? (int)(q0 - chunk_base) : 0);
+                const float4 lo = *reinterpret_cast<const float4*>(lds_hr + slot);
+                const float4 hi = *reinterpret_cast<const float4*>(lds_hr + slot + 256);
+                f[s].v[0] = lo.x; f[s].v[1] = lo.y; f[s].v[2] = lo.z; f[s].v[3] = lo.w;
+                f[s].v[4] = hi.x; f[s].v[5] = hi.y; f[s].v[6] = hi.z; f[s].v[7] = hi.w;
+                w[s].unpack(ahead[s]);
+            } else {
+                Chunk8<DT> raw;
+                raw.load_vec(W, row_off_ld + q_ld);
+                f[s].load_vec(hr, q_ld);
+                w[s].unpack(raw);
+            }
         }
+        if (STAGED && span + 1 < nspans) request(span + 1);
 #pragma unroll
         for (int s = 0; s < kSegs; ++s) {
 #pragma unroll
@@ -224,7 +305,7 @@ __global__ __launch_bounds__(kTeamThreads) void ewma_team_kernel(
 #pragma unroll
         for (int s = 0; s < kSegs; ++s) {
             const int64_t q0 = q_run + (int64_t)s * 512;
-            const bool on = q0 < cols;
+            const bool on = FULL || q0 < cols;
             const float yin = fmaf(shift_y[s], enter_y, y_in[s]);
             bool prune[8];
             // the row's first weight is never pruned (est starts at its score, dev at 0); in scaled form
@@ -237,10 +318,17 @@ __global__ __launch_bounds__(kTeamThreads) void ewma_team_kernel(
             const uint32_t keep = on ? (gone ^ 0xffu) : 0u;
             pruned += on ? __popc(gone) : 0;
             const uint32_t word = quad_gather_bytes(keep, lane);
-            if ((lane & 3) == 0 && on) keep_mask[row * mask_words + (q0 >> 5)] = word;
-            if (apply && on) w[s].store_pruned(W, row_off + q0, prune);
+            // the four lanes of a quad hold the same word; in a FULL span all of them store it
+            if (FULL || ((lane & 3) == 0 && on)) keep_mask[row * mask_words + (q0 >> 5)] = word;
+            if (APPLY && on) w[s].store_pruned(W, row_off + q0, prune);
         }
-    }
+    };
+    // spans that end inside the row: only a wavefront that has a row takes the unpredicated code (the choice is
+    // uniform per wavefront, and both versions meet the same barriers)
+    const int full_spans = has_row ? (int)(in / span_cols) : 0;
+    int span = 0;
+    for (; span < full_spans; ++span) work(span, std::true_type());
+    for (; span < nspans; ++span) work(span, std::false_type());
 
     // counts: unconditional, so that every wavefront of the workgroup meets the barrier
     {
@@ -263,11 +351,19 @@ __global__ __launch_bounds__(kTeamThreads) void ewma_team_kernel(
 
 template <int DT, int NW>
 static hipError_t launch_team_t(const RowGroups& g, int64_t in, const float* hr, const EwmaConsts& c, bool apply,
-                                hipStream_t stream) {
+                                bool staged, hipStream_t stream) {
     constexpr int rows = 4 / NW;
     const int64_t groups = ((int64_t)g.total() + rows - 1) / rows;
-    hipLaunchKernelGGL((ewma_team_kernel<DT, NW>), dim3((unsigned)groups), dim3(kTeamThreads), 0, stream, g, in, hr, c,
-                       apply ? 1 : 0);
+    const dim3 grid((unsigned)groups), block(kTeamThreads);
+    const size_t lds = staged ? (size_t)kStagedCols * sizeof(float) : 0;
+    if (staged && apply)
+        hipLaunchKernelGGL((ewma_team_kernel<DT, NW, true, true>), grid, block, lds, stream, g, in, hr, c);
+    else if (staged)
+        hipLaunchKernelGGL((ewma_team_kernel<DT, NW, true, false>), grid, block, lds, stream, g, in, hr, c);
+    else if (apply)
+        hipLaunchKernelGGL((ewma_team_kernel<DT, NW, false, true>), grid, block, lds, stream, g, in, hr, c);
+    else
+        hipLaunchKernelGGL((ewma_team_kernel<DT, NW, false, false>), grid, block, lds, stream, g, in, hr, c);
     return hipGetLastError();
 }
 
@@ -287,16 +383,20 @@ RowGroups single_matrix(const void* W, int64_t out, int64_t ldw, uint32_t* keep_
 // team size: `team` = 1, 2 or 4 wavefronts per row; 0 picks by the number of rows
 hipError_t launch_ewma_team(const RowGroups& g, int64_t in, int dt, const float* hr, const EwmaConsts& c,
                             bool apply, int team, hipStream_t stream) {
-    // at least four wavefronts per SIMD (1024 SIMDs) before a row gets a wavefront to itself
+    // at least four wavefronts per SIMD (1024 SIMDs) before a row gets a wavefront to itself; rows more than
+    // twice as long as the matrix is tall are shared by two wavefronts (measured 4-9 % faster on the wide
+    // projections: half the spans a wavefront walks in sequence, for two barriers per span)
     const int64_t out = g.total();
-    if (team == 0) team = read_tuning().team;  // measurement override
-    if (team == 0) team = out <= 1024 ? 4 : (out <= 2048 ? 2 : 1);
+    const Tuning tune = read_tuning();  // measurement overrides
+    if (team == 0) team = tune.team;
+    if (team == 0) team = out <= 1024 ? 4 : ((out <= 2048 || in > 2 * out) ? 2 : 1);
+    const bool st = !tune.select_direct;
     return with_dtype(dt, [&](auto tag) {
         constexpr int DT = decltype(tag)::value;
         switch (team) {
-            case 4: return launch_team_t<DT, 4>(g, in, hr, c, apply, stream);
-            case 2: return launch_team_t<DT, 2>(g, in, hr, c, apply, stream);
-            default: return launch_team_t<DT, 1>(g, in, hr, c, apply, stream);
+            case 4: return launch_team_t<DT, 4>(g, in, hr, c, apply, st, stream);
+            case 2: return launch_team_t<DT, 2>(g, in, hr, c, apply, st, stream);
+            default: return launch_team_t<DT, 1>(g, in, hr, c, apply, st, stream);
         }
     });
 }

@@ -480,3 +480,33 @@ def test_launch_shape_overrides_keep_results(orc, gpu, monkeypatch):
         torch.cuda.synchronize()
         assert np.array_equal(mask_to_host(buf.keep_mask), nm_o)
         assert same_bits(synth.torch_to_host_bits(W), orc.apply(Wh.copy(), nm_o))
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_ewma_team_sizes_and_staging_agree_with_oracle(orc, gpu, monkeypatch, dtype):
+    """Every way the fast EWMA kernel can be cut - 1, 2 or 4 wavefronts per row, channel factors staged in LDS
+    with the weights requested a span ahead or everything loaded directly - on a row that spans several
+    staged chunks and ends in a ragged span, with and without the fused apply, and with a last row group that
+    is only partly filled: the masks meet the oracle under the per-element threshold rule and the applied
+    weights are the oracle's apply of that mask."""
+    import torch
+    from paper_2501_16376_amd import binding as b, synth
+    from gpu_util import to_device, check_ewma_mask, mask_to_host, same_bits
+    out, n = 131, 9000                                            # 9000 = 2 chunks of 4096 + 808 columns
+    Wh, Xh = synth.layer_inputs(out, n, 64, seed=4242, dtype=dtype)
+    _, _, hr_o = orc.layer_stats(Xh)
+    hr_dev = to_device(hr_o, gpu)
+    buf = b.LayerBuffers(out, n, 8, gpu)
+    for setting in ("1", "2", "4", "1,direct", "2,direct", "4,direct", "0", "0,direct"):
+        monkeypatch.setenv("SWIFTPRUNE_SELECT_TEAM", setting)
+        for flags in (0, b.SP_APPLY_INPLACE):
+            W = to_device(Wh, gpu)
+            buf.keep_mask.zero_()
+            buf.row_pruned.fill_(-1)
+            b.swiftprune_score_select(W, hr_dev, buf.keep_mask, la=0.5, row_pruned=buf.row_pruned, flags=flags)
+            torch.cuda.synchronize()
+            m = mask_to_host(buf.keep_mask)
+            check_ewma_mask(orc, Wh, hr_o, A, B, 0.5, m, buf.row_pruned.cpu().numpy())
+            want = orc.apply(Wh.copy(), m) if flags else Wh
+            assert same_bits(synth.torch_to_host_bits(W), want), (setting, flags)
