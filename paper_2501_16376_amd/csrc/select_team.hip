@@ -150,7 +150,6 @@ __global__ __launch_bounds__(kTeamThreads) void ewma_team_kernel(
     int pruned = 0;
     // lanes past the end of the row (and wavefronts without a row) read valid memory and compute on it, but
     // store nothing: whatever they compute can only reach columns to their right, which do not exist either
-    const int64_t row_off_ld = row_off;
     const int64_t lane_col = (int64_t)part * (kSegs * 512) + (int64_t)lane * 8;
 
     Chunk8<DT> ahead[kSegs];  // STAGED: the weights of the span to come
@@ -158,7 +157,7 @@ __global__ __launch_bounds__(kTeamThreads) void ewma_team_kernel(
 #pragma unroll
         for (int s = 0; s < kSegs; ++s) {
             const int64_t q0 = (int64_t)span * span_cols + lane_col + (int64_t)s * 512;
-            ahead[s].load_vec(W, row_off_ld + (q0 < cols ? q0 : 0));
+            ahead[s].load_vec(W, row_off + (q0 < cols ? q0 : 0));
         }
     };
     // STAGED: kStagedCols factors at a time sit in LDS; a chunk is replaced every kStageSpans spans, by all
@@ -212,15 +211,15 @@ __global__ __launch_bounds__(kTeamThreads) void ewma_team_kernel(
             const int64_t q0 = q_run + (int64_t)s * 512;
             const int64_t q_ld = (FULL || q0 < cols) ? q0 : 0;
             if (STAGED) {
-                const int slot = staged_slot((FULL || q0 < cols) ? (int)(q0 - chunk_base) : 0);
-                const float4 lo = *reinterpret_cast<const float4*>(lds_hr + slot);
-                const float4 hi = *reinterpret_cast<const float4*>(lds_hr + slot + 256);
+                const int at = staged_slot((FULL || q0 < cols) ? (int)(q0 - chunk_base) : 0);
+                const float4 lo = *reinterpret_cast<const float4*>(lds_hr + at);
+                const float4 hi = *reinterpret_cast<const float4*>(lds_hr + at + 256);
                 f[s].v[0] = lo.x; f[s].v[1] = lo.y; f[s].v[2] = lo.z; f[s].v[3] = lo.w;
                 f[s].v[4] = hi.x; f[s].v[5] = hi.y; f[s].v[6] = hi.z; f[s].v[7] = hi.w;
                 w[s].unpack(ahead[s]);
             } else {
                 Chunk8<DT> raw;
-                raw.load_vec(W, row_off_ld + q_ld);
+                raw.load_vec(W, row_off + q_ld);
                 f[s].load_vec(hr, q_ld);
                 w[s].unpack(raw);
             }
