@@ -62,6 +62,7 @@ _vp, _i64, _i32, _f, _d = C.c_void_p, C.c_int64, C.c_int, C.c_float, C.c_double
 
 def _declare(L: C.CDLL) -> C.CDLL:
     L.oracle_stats_accumulate.argtypes = [_vp, _i64, _i64, _i64, _i32, _vp]
+    L.oracle_stats_accumulate_partials.argtypes = [_vp, _i64, _i64, _i64, _vp]
     L.oracle_stats_finalize.argtypes = [_vp, _i64, _vp, _vp]
     L.oracle_channel_factor_f32.argtypes = [_vp, _f, _i64, _vp]
     L.oracle_channel_factor_f64.argtypes = [_vp, _i64, _vp]
@@ -79,7 +80,7 @@ def _declare(L: C.CDLL) -> C.CDLL:
     L.oracle_compact_nm.argtypes = [_vp, _i64, _i64, _i64, _i32, _vp, _i32, _i32, _vp, _vp]
     L.oracle_expand_nm.argtypes = [_vp, _vp, _i64, _i64, _i32, _i32, _i32, _vp]
     L.oracle_apply.argtypes = [_vp, _i64, _i64, _i64, _i32, _vp]
-    for name in ("oracle_stats_accumulate", "oracle_stats_finalize", "oracle_channel_factor_f32",
+    for name in ("oracle_stats_accumulate", "oracle_stats_accumulate_partials", "oracle_stats_finalize", "oracle_channel_factor_f32",
                  "oracle_channel_factor_f64", "oracle_score_f32", "oracle_score_f64",
                  "oracle_ewma_row_f32", "oracle_ewma_row_f64", "oracle_ewma_select_f32",
                  "oracle_ewma_select_f64", "oracle_nm_select_f32", "oracle_nm_select_f64",
@@ -126,6 +127,18 @@ def stats_accumulate(X: np.ndarray, acc: np.ndarray | None = None, L=None) -> np
         acc = np.zeros(n, dtype=np.float64)
     assert acc.dtype == np.float64 and acc.shape == (n,) and acc.flags.c_contiguous
     (L or lib()).oracle_stats_accumulate(ptr, tokens, n, ld, dt, acc.ctypes.data)
+    return acc
+
+
+def stats_accumulate_partials(P: np.ndarray, acc: np.ndarray | None = None, L=None) -> np.ndarray:
+    """acc[q] += sum_p P[p,q] in double, P float32 [parts, in] (row pitch allowed): the sums of squares that the
+    producer of X formed over its own pieces of the tokens.  Returns acc (created when None)."""
+    assert P.dtype == np.float32 and P.ndim == 2 and P.strides[1] == 4 and P.strides[0] % 4 == 0
+    parts, n = P.shape
+    if acc is None:
+        acc = np.zeros(n, dtype=np.float64)
+    assert acc.dtype == np.float64 and acc.shape == (n,) and acc.flags.c_contiguous
+    (L or lib()).oracle_stats_accumulate_partials(P.ctypes.data, parts, n, P.strides[0] // 4, acc.ctypes.data)
     return acc
 
 

@@ -100,6 +100,21 @@ void oracle_stats_accumulate(const void *X, int64_t tokens, int64_t in, int64_t 
 }
 
 /*
+ * The same sums when the producer of X has already added up the squares of its own share of the
+ * tokens (Algorithm 1, first statement, with the sum over tokens cut in `parts` pieces):
+ * P[p*ld + q] = sum of X[t,q]^2 over the tokens of piece p, stored as float.
+ *     acc[q] += (double)P[p][q],  p ascending.
+ */
+void oracle_stats_accumulate_partials(const float *P, int64_t parts, int64_t in, int64_t ld, double *acc)
+{
+    for (int64_t p = 0; p < parts; ++p) {
+        for (int64_t q = 0; q < in; ++q) {
+            acc[q] += (double)P[p * ld + q];
+        }
+    }
+}
+
+/*
  * xsq[q] = (float)acc[q];  S = (float)(sum_q acc[q]) summed in double, q ascending.
  */
 void oracle_stats_finalize(const double *acc, int64_t in, float *xsq, float *S)

@@ -213,6 +213,32 @@ def pin_stats_library_sum(orc, L=None):
     assert np.all(hr1 == np.float32(0.5) / (np.float32(1) - np.float32(1 / 64)))
 
 
+def pin_stats_from_partials(orc, L=None):
+    """Statistics from sums that the producer of X formed over its own pieces of the tokens: the column sum
+    of the pieces (numpy, float64), with a row pitch, continued over two calls; and the property that makes
+    the entry point useful - cutting the tokens of X into pieces (of unequal length), squaring and summing
+    each piece exactly, and combining the pieces gives the statistics of X itself."""
+    rng = _rng(31)
+    P = rng.lognormal(0.0, 1.0, (7, 40)).astype(np.float32)
+    Pp = np.full((7, 48), 1e9, dtype=np.float32)              # pitch > in: the padding must be ignored
+    Pp[:, :40] = P
+    acc = orc.stats_accumulate_partials(Pp[:, :40], L=L)
+    ref = P.astype(np.float64).sum(0)
+    assert np.allclose(acc, ref, rtol=1e-15)
+    acc2 = orc.stats_accumulate_partials(Pp[:3, :40], L=L)
+    acc2 = orc.stats_accumulate_partials(Pp[3:, :40], acc2, L=L)
+    assert np.allclose(acc2, ref, rtol=1e-15)
+    one = orc.stats_accumulate_partials(np.ascontiguousarray(P[2:3]), L=L)   # a single piece is returned as it is
+    assert np.array_equal(one, P[2].astype(np.float64))
+    # pieces of X: small integers, so that every square and every sum is exact in float and in double
+    X = rng.integers(-8, 9, size=(90, 24)).astype(np.float32)
+    cuts = [0, 13, 14, 50, 90]
+    pieces = np.stack([np.square(X[a:b].astype(np.float64)).sum(0) for a, b in zip(cuts[:-1], cuts[1:])]).astype(np.float32)
+    xsq_p, S_p = orc.stats_finalize(orc.stats_accumulate_partials(pieces, L=L), L=L)
+    xsq_x, S_x, _ = orc.layer_stats(X, L=L)
+    assert np.array_equal(xsq_p, xsq_x) and S_p == S_x
+
+
 def pin_inverse_identity(orc, L=None):
     """The score's denominator is the paper's surrogate for the diagonal of the damped inverse Hessian.
 
@@ -621,7 +647,7 @@ def pin_binary16_storage(orc, L=None):
 
 
 ALL_PINS = [pin_binary16_storage, pin_topk_is_library_sort, pin_compact_nm, pin_tracks_mean_and_deviation, pin_worked_rows, pin_closed_form, pin_constant_row, pin_first_two_elements,
-            pin_monotone_in_la, pin_step_response, pin_stats_library_sum, pin_inverse_identity,
+            pin_monotone_in_la, pin_step_response, pin_stats_library_sum, pin_stats_from_partials, pin_inverse_identity,
             pin_float_factor_matches_double, pin_select_metamorphic,
             pin_uniform_energy_reduces_to_magnitude, pin_nm_invariants,
             pin_channel_energy_changes_ranking, pin_literal_form, pin_apply, pin_sort_comparator]

@@ -38,6 +38,12 @@ MUTANTS = [
      "else keep_mask[r * words + (q >> 5)] |= (uint32_t)1 << (31 - (q & 31));"),
     ("stats_not_squared", "swiftprune_oracle.c", "acc[q] += x * x;", "acc[q] += fabs(x);"),
     ("stats_ignores_pitch", "swiftprune_oracle.c", "load_elem(X, t * ldx + q, dt)", "load_elem(X, t * in + q, dt)"),
+    ("partials_ignore_pitch", "swiftprune_oracle.c", "acc[q] += (double)P[p * ld + q];", "acc[q] += (double)P[p * in + q];"),
+    ("partials_squared_again", "swiftprune_oracle.c", "acc[q] += (double)P[p * ld + q];",
+     "acc[q] += (double)P[p * ld + q] * (double)P[p * ld + q];"),
+    ("partials_skip_first_piece", "swiftprune_oracle.c", "for (int64_t p = 0; p < parts; ++p) {\n        for (int64_t q = 0; q < in; ++q) {\n            acc[q] += (double)P",
+     "for (int64_t p = 1; p < parts; ++p) {\n        for (int64_t q = 0; q < in; ++q) {\n            acc[q] += (double)P"),
+    ("partials_overwrite", "swiftprune_oracle.c", "acc[q] += (double)P[p * ld + q];", "acc[q] = (double)P[p * ld + q];"),
     ("factor_plus", "swiftprune_oracle.c", "float den = 1.0f - rho;\n        if (!(den > 0.0f))\n            den = FLT_EPSILON;\n        hr[q] = 0.5f / den;",
      "float den = 1.0f + rho;\n        if (!(den > 0.0f))\n            den = FLT_EPSILON;\n        hr[q] = 0.5f / den;"),
     ("factor_f64_no_half", "swiftprune_oracle.c", "hr[q] = 0.5 / den;", "hr[q] = 1.0 / den;"),
