@@ -480,8 +480,15 @@ def chunked_stats(sp, torch, stack, stream, chunks=8, reps=10):
     def whole():
         sp.swiftprune_layer_stats(X, b.xsq, b.S, b.hr, workspace=b.workspace, stream=stream)
 
+    # the producer has summed the squares of its own 256 pieces of the tokens: nothing of X is read
+    parts = 256
+    P = torch.rand((parts, n), dtype=torch.float32, device=stack.dev) * (T / parts)
+
+    def from_partials():
+        sp.swiftprune_layer_stats_from_partials(P, b.xsq, b.S, b.hr, stream=stream)
+
     out = {}
-    for name, fn in (("whole", whole), ("chunked", chunked)):
+    for name, fn in (("from_partials", from_partials), ("whole", whole), ("chunked", chunked)):
         fn()
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -495,7 +502,10 @@ def chunked_stats(sp, torch, stack, stream, chunks=8, reps=10):
     return {"workload": f"statistics of one {T} x {n} layer input in {chunks} token chunks (accumulate mode)",
             "chunks": chunks, "us_chunked": round(out["chunked"], 1), "us_single_call": round(out["whole"], 1),
             "hbm_frac_chunked": round(nbytes / out["chunked"] / 1e3 / HBM_PEAK_GBS, 4),
-            "hbm_frac_single_call": round(nbytes / out["whole"] / 1e3 / HBM_PEAK_GBS, 4)}
+            "hbm_frac_single_call": round(nbytes / out["whole"] / 1e3 / HBM_PEAK_GBS, 4),
+            "us_from_256_producer_partials": round(out["from_partials"], 1),
+            "from_partials_note": "swiftprune_layer_stats_from_partials on 256 per-piece sums of squares (random values "
+                                  "here): what remains of step 1 when the kernel that writes X also sums its squares"}
 
 
 def sample_70b(sp, synth, torch, dev, stream, T, storage, blocks, steps):

@@ -109,6 +109,26 @@ int swiftprune_layer_stats_static(const void *X, int64_t tokens, int64_t in, int
                                   void *hip_stream);
 
 /*
+ * Step 1 from sums that the producer of X has formed itself (Algorithm 1, first statement: x_q^2 is a sum over
+ * the calibration tokens, so it can be cut in pieces anywhere; Sec. 3.1: S and the score's denominator).  A kernel
+ * that writes X (a GEMM or activation epilogue) adds up the squares of what it writes, per channel, over its own
+ * piece of the tokens, and stores one fp32 row per piece; this call adds the pieces in fp64 and finishes the step.
+ * Nothing of X is read, so the 2 bytes per activation that swiftprune_layer_stats streams are saved altogether.
+ *   partials [parts, ld] fp32, row-major (device, read): partials[p*ld + q] = sum over the tokens of piece p of
+ *            X[t,q]^2; parts >= 1 (at most 2^24), ld >= in; pieces may cover any numbers of tokens
+ *   xsq      [in] fp32 (device): accumulate == 0: written; != 0: the pieces are added to what it holds
+ *   S        [1]  fp32 (device, written): the sum over q of the xsq just written, formed in fp64 (with
+ *            accumulate != 0 it is formed from the accumulated xsq; the old value is not read)
+ *   hr       [in] fp32 (device): written when finalize != 0, as by swiftprune_layer_stats (same conventions for
+ *            S == 0 and a non-positive denominator); may be NULL when finalize == 0
+ * Two small launches on `hip_stream`; no workspace.  Errors: SP_EINVAL (null pointer, parts / in <= 0, ld < in,
+ * misaligned pointer), SP_EHIP; nothing is enqueued on SP_EINVAL.
+ */
+int swiftprune_layer_stats_from_partials(const float *partials, int64_t parts, int64_t in, int64_t ld,
+                                         float *xsq, float *S, float *hr, int accumulate, int finalize,
+                                         void *hip_stream);
+
+/*
  * The last part of step 1 on its own (denominator of the Sec. 3.1 score equation):
  *     hr[q] = 1/2 / (1 - xsq[q]/S),  with the conventions of swiftprune_layer_stats for S == 0 and a
  *     non-positive denominator.

@@ -19,7 +19,7 @@ SP_OK, SP_EINVAL, SP_ENOSPC, SP_EHIP, SP_ERANGE = 0, -1, -2, -3, -4
 SP_SEQUENTIAL_ORDER, SP_APPLY_INPLACE = 1, 2
 
 EXPORTS = ("swiftprune_layer_stats", "swiftprune_layer_stats_static", "swiftprune_score_select", "swiftprune_nm_select",
-           "swiftprune_apply", "swiftprune_score_select_group", "swiftprune_nm_select_group", "swiftprune_channel_factor", "swiftprune_ewma_trace", "swiftprune_count_pruned", "swiftprune_calibrate_la", "swiftprune_calibrate_la_device", "swiftprune_la_workspace_bytes", "swiftprune_score_select_la", "swiftprune_topk_select", "swiftprune_compact_nm", "swiftprune_expand_nm", "swiftprune_nm_meta_words", "swiftprune_la_for_sparsity", "swiftprune_stats_workspace_bytes",
+           "swiftprune_apply", "swiftprune_score_select_group", "swiftprune_nm_select_group", "swiftprune_channel_factor", "swiftprune_layer_stats_from_partials", "swiftprune_ewma_trace", "swiftprune_count_pruned", "swiftprune_calibrate_la", "swiftprune_calibrate_la_device", "swiftprune_la_workspace_bytes", "swiftprune_score_select_la", "swiftprune_topk_select", "swiftprune_compact_nm", "swiftprune_expand_nm", "swiftprune_nm_meta_words", "swiftprune_la_for_sparsity", "swiftprune_stats_workspace_bytes",
            "swiftprune_strerror", "swiftprune_version")
 
 
@@ -73,6 +73,8 @@ def load_library(path: str | None = None) -> C.CDLL:
     L.swiftprune_apply.restype = i32
     L.swiftprune_channel_factor.argtypes = [vp, vp, i64, vp, vp]
     L.swiftprune_channel_factor.restype = i32
+    L.swiftprune_layer_stats_from_partials.argtypes = [vp, i64, i64, i64, vp, vp, vp, i32, i32, vp]
+    L.swiftprune_layer_stats_from_partials.restype = i32
     L.swiftprune_ewma_trace.argtypes = [vp, i64, i64, i64, i32, vp, f, f, vp, vp, vp]
     L.swiftprune_ewma_trace.restype = i32
     L.swiftprune_count_pruned.argtypes = [vp, i64, i64, i64, i32, vp, f, f, C.POINTER(C.c_float), i32, vp, vp]
@@ -205,6 +207,20 @@ def swiftprune_channel_factor(xsq, S, hr, stream=None):
         _vec(xsq, torch.float32, n_in, "xsq"), _vec(S, torch.float32, 1, "S"), n_in,
         _vec(hr, torch.float32, n_in, "hr"), _stream(stream))
     _check(code, "swiftprune_channel_factor")
+
+
+def swiftprune_layer_stats_from_partials(partials, xsq, S, hr=None, accumulate: bool = False, finalize: bool = True,
+                                         stream=None):
+    """Step 1 from partials[parts, in] (fp32 GPU tensor, unit column stride): per-piece sums of X^2 that the
+    producer of X formed over its own share of the tokens.  Writes xsq, S and (finalize) hr."""
+    import torch
+    ptr, parts, n_in, ld, dt = _matrix(partials)
+    if dt != SP_F32:
+        raise ValueError("partials must be float32")
+    code = load_library().swiftprune_layer_stats_from_partials(
+        ptr, parts, n_in, ld, _vec(xsq, torch.float32, n_in, "xsq"), _vec(S, torch.float32, 1, "S"),
+        _vec(hr, torch.float32, n_in, "hr"), int(bool(accumulate)), int(bool(finalize)), _stream(stream))
+    _check(code, "swiftprune_layer_stats_from_partials")
 
 
 def swiftprune_score_select(W, hr, keep_mask, sparsity: float = 0.5, alpha: float = 0.125,

@@ -8,7 +8,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libswiftprune.so")
-SOURCES = ["api.hip", "stats.hip", "stats_static.hip", "select_scan.hip", "select_team.hip", "select_seq.hip", "nm_apply.hip", "calibrate.hip", "topk.hip", "compact.hip", "trace.hip"]
+SOURCES = ["api.hip", "stats.hip", "stats_static.hip", "stats_partials.hip", "select_scan.hip", "select_team.hip", "select_seq.hip", "nm_apply.hip", "calibrate.hip", "topk.hip", "compact.hip", "trace.hip"]
 
 # -ffp-contract=off: multiply-adds are fused only where the source says fmaf(), so the
 # strict-order kernel rounds every operation on its own.

@@ -136,6 +136,19 @@ int swiftprune_channel_factor(const float* xsq, const float* S, int64_t in, floa
     return e == hipSuccess ? SP_OK : SP_EHIP;
 }
 
+int swiftprune_layer_stats_from_partials(const float* partials, int64_t parts, int64_t in, int64_t ld, float* xsq,
+                                         float* S, float* hr, int accumulate, int finalize, void* hip_stream) {
+    if (partials == nullptr || xsq == nullptr || S == nullptr || (finalize && hr == nullptr)) return SP_EINVAL;
+    if (parts <= 0 || in <= 0 || ld < in) return SP_EINVAL;
+    if (parts > ((int64_t)1 << 24) || in > (int64_t)0x7fffffff * 64) return SP_EINVAL;
+    if (reinterpret_cast<uintptr_t>(partials) % 4 != 0 || reinterpret_cast<uintptr_t>(xsq) % 4 != 0 ||
+        reinterpret_cast<uintptr_t>(S) % 4 != 0 || (hr != nullptr && reinterpret_cast<uintptr_t>(hr) % 4 != 0))
+        return SP_EINVAL;
+    const hipError_t e = sp::launch_stats_from_pieces(partials, parts, in, ld, xsq, S, hr, accumulate, finalize,
+                                                      static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? SP_OK : SP_EHIP;
+}
+
 int swiftprune_score_select(const void* W, int64_t out, int64_t in, int64_t ldw, sp_dtype dt,
                             const float* hr, float sparsity, const sp_ewma_params* params,
                             uint32_t* keep_mask, int32_t* row_pruned, float* scores,

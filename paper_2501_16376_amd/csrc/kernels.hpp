@@ -84,6 +84,9 @@ hipError_t launch_ewma_sequential(const void* W, int64_t out, int64_t in, int64_
                                   hipStream_t stream);
 
 hipError_t launch_channel_factor(const float* xsq, const float* S, int64_t in, float* hr, hipStream_t stream);
+// statistics from per-piece sums of squares formed by the producer of X (stats_partials.hip)
+hipError_t launch_stats_from_pieces(const float* P, int64_t parts, int64_t in, int64_t ld, float* xsq, float* S,
+                                    float* hr, int accumulate, int finalize, hipStream_t stream);
 
 // ---- est / dev sequences written out (diagnostic) ----
 hipError_t launch_ewma_trace(const void* W, int64_t out, int64_t in, int64_t ldw, int dt, bool vec,

@@ -150,6 +150,12 @@ def test_argument_checks_do_not_launch(lib):
     cf = lib.swiftprune_channel_factor
     assert cf(None, p, 8, p, None) == E and cf(p, None, 8, p, None) == E and cf(p, p, 8, None, None) == E
     assert cf(p, p, 0, p, None) == E and cf(p + 2, p, 8, p, None) == E
+    fp = lib.swiftprune_layer_stats_from_partials
+    assert fp(None, 4, 8, 8, p, p, p, 0, 1, None) == E and fp(p, 4, 8, 8, None, p, p, 0, 1, None) == E
+    assert fp(p, 4, 8, 8, p, None, p, 0, 1, None) == E and fp(p, 4, 8, 8, p, p, None, 0, 1, None) == E   # finalize needs hr
+    assert fp(p, 0, 8, 8, p, p, p, 0, 1, None) == E and fp(p, 4, 0, 8, p, p, p, 0, 1, None) == E
+    assert fp(p, 4, 8, 7, p, p, p, 0, 1, None) == E                          # pitch < columns
+    assert fp(p + 2, 4, 8, 8, p, p, p, 0, 1, None) == E and fp(p, (1 << 24) + 1, 8, 8, p, p, p, 0, 1, None) == E
     tr = lib.swiftprune_ewma_trace
     assert tr(p, 8, 8, 8, 1, p, 0.125, 0.125, None, None, None) == E         # nothing to write
     assert tr(None, 8, 8, 8, 1, p, 0.125, 0.125, p, p, None) == E

@@ -510,3 +510,54 @@ def test_ewma_team_sizes_and_staging_agree_with_oracle(orc, gpu, monkeypatch, dt
             check_ewma_mask(orc, Wh, hr_o, A, B, 0.5, m, buf.row_pruned.cpu().numpy())
             want = orc.apply(Wh.copy(), m) if flags else Wh
             assert same_bits(synth.torch_to_host_bits(W), want), (setting, flags)
+
+
+@pytest.mark.parametrize("tokens,n,parts,dtype", [(3000, 2056, 37, "bf16"), (513, 1000, 1, "f32"), (4096, 4096, 256, "bf16"),
+                                                  (700, 72, 700, "f32")])
+def test_layer_stats_from_partials(orc, gpu, tokens, n, parts, dtype):
+    """Statistics from per-piece sums of squares, as the producer of X would hand them over: xsq, S and the
+    factors equal the oracle's combination of the same pieces (fp64 sums on both sides, so 1e-6 relative is
+    rounding slack, not tolerance), agree with the statistics of X itself to 1e-5, continue over two calls in
+    accumulate mode, and feed the selection like any other factor vector."""
+    import torch
+    from paper_2501_16376_amd import binding as b, synth
+    from gpu_util import to_device, mask_to_host, check_ewma_mask
+    say(f"[case] stats from partials tokens={tokens} in={n} parts={parts} {dtype}")
+    Wh, Xh = synth.layer_inputs(24, n, tokens, seed=tokens + n, dtype=dtype)
+    Xf = synth.bf16_bits_to_f32(Xh) if dtype == "bf16" else Xh
+    cuts = np.linspace(0, tokens, parts + 1).astype(np.int64)        # pieces of unequal length
+    pieces = np.stack([np.square(Xf[a:c].astype(np.float64)).sum(0) for a, c in zip(cuts[:-1], cuts[1:])]).astype(np.float32)
+    padded = np.full((parts, n + 12), 7e8, dtype=np.float32)          # a row pitch; the padding must not be read as data
+    padded[:, :n] = pieces
+    xsq_o, S_o = orc.stats_finalize(orc.stats_accumulate_partials(pieces))
+    hr_o = orc.channel_factor_f32(xsq_o, S_o)
+    P = torch.from_numpy(padded).to(gpu)[:, :n]
+    xsq = torch.full((n,), -1.0, dtype=torch.float32, device=gpu)
+    S = torch.full((1,), -1.0, dtype=torch.float32, device=gpu)
+    hr = torch.full((n,), -1.0, dtype=torch.float32, device=gpu)
+    b.swiftprune_layer_stats_from_partials(P, xsq, S, hr)
+    torch.cuda.synchronize()
+    assert np.allclose(xsq.cpu().numpy(), xsq_o, rtol=1e-6, atol=0)
+    assert np.isclose(float(S.item()), float(S_o), rtol=1e-6, atol=0)
+    assert np.allclose(hr.cpu().numpy(), hr_o, rtol=1e-6, atol=0)
+    xsq_x, S_x, hr_x = orc.layer_stats(Xh)                            # the statistics of X itself
+    assert np.allclose(xsq.cpu().numpy(), xsq_x, rtol=1e-5, atol=0) and np.isclose(float(S.item()), float(S_x), rtol=1e-5)
+    assert np.allclose(hr.cpu().numpy(), hr_x, rtol=1e-5, atol=0)
+    if parts >= 2:                                                    # two calls: first pieces, then the rest on top
+        k = parts // 3 + 1
+        xsq2 = torch.empty_like(xsq)
+        S2 = torch.empty_like(S)
+        hr2 = torch.full_like(hr, -1.0)
+        b.swiftprune_layer_stats_from_partials(P[:k], xsq2, S2, None, accumulate=False, finalize=False)
+        torch.cuda.synchronize()
+        assert np.all(hr2.cpu().numpy() == -1.0)                      # not finalised: the factors are untouched
+        b.swiftprune_layer_stats_from_partials(P[k:], xsq2, S2, hr2, accumulate=True, finalize=True)
+        torch.cuda.synchronize()
+        assert np.allclose(xsq2.cpu().numpy(), xsq_o, rtol=1e-6, atol=0) and np.isclose(float(S2.item()), float(S_o), rtol=1e-6)
+        assert np.allclose(hr2.cpu().numpy(), hr_o, rtol=1e-6, atol=0)
+    if n % 8 == 0 and dtype == "bf16" and n <= 2056:                  # and the factors serve the selection
+        mask = torch.empty((24, (n + 31) // 32), dtype=torch.int32, device=gpu)
+        cnt = torch.empty(24, dtype=torch.int32, device=gpu)
+        b.swiftprune_score_select(to_device(Wh, gpu), hr, mask, la=0.5, row_pruned=cnt)
+        torch.cuda.synchronize()
+        check_ewma_mask(orc, Wh, hr_o, A, B, 0.5, mask_to_host(mask), cnt.cpu().numpy())   # the oracle keeps its own factors
