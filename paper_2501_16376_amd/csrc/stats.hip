@@ -232,7 +232,9 @@ __global__ __launch_bounds__(kCombineThreads) void stats_combine_kernel(
     double gs = 0.0;
     for (int i = threadIdx.x; i < ngroups; i += kCombineThreads) gs += group_sums[i];
     double S_d = block_sum_256(gs, lds4);
-    if (accumulate) S_d += (double)S_io[0];
+    // the running S is read by everybody only when the factors are due; otherwise workgroup 0 alone reads
+    // and rewrites it
+    if (accumulate && (finalize || blockIdx.x == 0)) S_d += (double)S_io[0];
     const float S = (float)S_d;
 
     double s = 0.0;
@@ -257,9 +259,9 @@ __global__ __launch_bounds__(kCombineThreads) void stats_combine_kernel(
         xsq[col] = x;
         if (finalize) hr[col] = channel_factor(x, S);
     }
-    // when accumulating, every workgroup reads the old S_io above, so the new value is stored by a
-    // separate launch; otherwise nobody reads it and workgroup 0 stores it here
-    if (!accumulate && blockIdx.x == 0 && threadIdx.x == 0) S_io[0] = S;
+    // when accumulating and finalising, every workgroup reads the old S_io above, so the new value is stored
+    // by a separate launch; otherwise nobody but workgroup 0 reads it and workgroup 0 stores it here
+    if (!(accumulate && finalize) && blockIdx.x == 0 && threadIdx.x == 0) S_io[0] = S;
 }
 
 // S[0] <- (accumulate ? S[0] : 0) + sum of the per-workgroup sums; same order as in the combine kernel
@@ -410,7 +412,7 @@ hipError_t launch_layer_stats(const void* X, int64_t tokens, int64_t in, int64_t
                        stream, partials, p.splits, p.units * p.epu, in, group_sums, ngroups, xsq,
                        accumulate, finalize, S, hr);
     e = hipGetLastError();
-    if (e != hipSuccess || !accumulate) return e;
+    if (e != hipSuccess || !(accumulate && finalize)) return e;
     hipLaunchKernelGGL(stats_total_kernel, dim3(1), dim3(kCombineThreads), 0, stream, group_sums, ngroups,
                        accumulate, S);
     return hipGetLastError();
