@@ -482,8 +482,7 @@ def test_launch_shape_overrides_keep_results(orc, gpu, monkeypatch):
         assert same_bits(synth.torch_to_host_bits(W), orc.apply(Wh.copy(), nm_o))
 
 
-@pytest.mark.gpu
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dtype", ["bf16", "f32", "f16"])
 def test_ewma_team_sizes_and_staging_agree_with_oracle(orc, gpu, monkeypatch, dtype):
     """Every way the fast EWMA kernel can be cut - 1, 2 or 4 wavefronts per row, channel factors staged in LDS
     with the weights requested a span ahead or everything loaded directly - on a row that spans several
