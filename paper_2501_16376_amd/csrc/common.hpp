@@ -221,14 +221,12 @@ __device__ __forceinline__ float score_of(float w, float factor) {
     return __fmul_rn(w2, factor);
 }
 
-// Packs eight per-lane decisions into bits 0..7 (bit k = p[k]) with one add-with-carry each:
-// acc <- 2 acc + p[k], k = 7 .. 0, the decision entering as the carry.
-__device__ __forceinline__ uint32_t pack_bits8(const bool* p) {
+// Packs eight per-lane decisions, given as lane masks (bit `lane` of m[k] = decision k of that lane), into
+// bits 0..7 of every lane (bit k = decision k) with one add-with-carry each: acc <- 2 acc + decision k,
+// k = 7 .. 0, the lane mask entering as the carry.
+__device__ __forceinline__ uint32_t pack_masks8(const uint64_t* m) {
     uint32_t acc = 0u;
-    const uint64_t b0 = __builtin_amdgcn_ballot_w64(p[0]), b1 = __builtin_amdgcn_ballot_w64(p[1]),
-                   b2 = __builtin_amdgcn_ballot_w64(p[2]), b3 = __builtin_amdgcn_ballot_w64(p[3]),
-                   b4 = __builtin_amdgcn_ballot_w64(p[4]), b5 = __builtin_amdgcn_ballot_w64(p[5]),
-                   b6 = __builtin_amdgcn_ballot_w64(p[6]), b7 = __builtin_amdgcn_ballot_w64(p[7]);
+    const uint64_t b0 = m[0], b1 = m[1], b2 = m[2], b3 = m[3], b4 = m[4], b5 = m[5], b6 = m[6], b7 = m[7];
     asm("v_addc_co_u32 %0, vcc, %0, %0, %8\n\t"
         "v_addc_co_u32 %0, vcc, %0, %0, %7\n\t"
         "v_addc_co_u32 %0, vcc, %0, %0, %6\n\t"
@@ -251,11 +249,13 @@ struct Unpacked8 {
 #pragma unroll
         for (int k = 0; k < 8; ++k) w[k] = c.get(k);
     }
-    // pruned entries become +0; bf16 / fp16 pairs are re-packed with one byte permute each
-    __device__ __forceinline__ void store_pruned(void* W, int64_t elem, const bool* prune) const {
+    // pruned entries (decisions given as lane masks) become +0: one select per weight that reads the mask from
+    // scalar registers, with no second comparison; bf16 / fp16 pairs are re-packed with one byte permute each
+    __device__ __forceinline__ void store_pruned_masks(void* W, int64_t elem, const uint64_t* gone) const {
         uint32_t z[8];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) z[k] = prune[k] ? 0u : __float_as_uint(w[k]);
+        for (int k = 0; k < 8; ++k)
+            asm("v_cndmask_b32_e64 %0, %1, 0, %2" : "=v"(z[k]) : "v"(w[k]), "s"(gone[k]));
         store_words(W, elem, z);
     }
     __device__ __forceinline__ void store_words(void* W, int64_t elem, const uint32_t* z) const {

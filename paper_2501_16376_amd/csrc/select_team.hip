@@ -196,8 +196,9 @@ __global__ __launch_bounds__(kTeamThreads) void ewma_team_kernel(
                 asm volatile("" : "+v"(ahead[s].raw[j]));
     }
 
-    auto work = [&](int span, auto full_tag) {
+    auto work = [&](int span, auto full_tag, auto more_tag) {
         constexpr bool FULL = decltype(full_tag)::value;
+        constexpr bool MORE = decltype(more_tag)::value;  // a span is known to follow (otherwise: looked up)
         const int64_t q_run = (int64_t)span * span_cols + lane_col;
         const int64_t chunk_base = (int64_t)(span - span % kStageSpans) * span_cols;  // first column of the staged chunk
         if (STAGED && span != 0 && span % kStageSpans == 0) stage(span);
@@ -224,7 +225,7 @@ __global__ __launch_bounds__(kTeamThreads) void ewma_team_kernel(
                 w[s].unpack(raw);
             }
         }
-        if (STAGED && span + 1 < nspans) request(span + 1);
+        if (STAGED && (MORE || span + 1 < nspans)) request(span + 1);
 #pragma unroll
         for (int s = 0; s < kSegs; ++s) {
 #pragma unroll
@@ -306,28 +307,33 @@ __global__ __launch_bounds__(kTeamThreads) void ewma_team_kernel(
             const int64_t q0 = q_run + (int64_t)s * 512;
             const bool on = FULL || q0 < cols;
             const float yin = fmaf(shift_y[s], enter_y, y_in[s]);
-            bool prune[8];
+            // decisions as lane masks: they feed the bit packing and the zeroing from scalar registers
+            uint64_t prune[8];
             // the row's first weight is never pruned (est starts at its score, dev at 0); in scaled form
             // that equality is only approximate, so it is stated
-            prune[0] = (x[s][0] > thr_scale * yin) && q0 != 0;
+            prune[0] = __builtin_amdgcn_ballot_w64((x[s][0] > thr_scale * yin) && q0 != 0);
 #pragma unroll
             for (int k = 1; k < 8; ++k)
-                prune[k] = x[s][k] > thr_scale * fmaf(c.B_pow[k], yin, y[s][k - 1]);
-            const uint32_t gone = pack_bits8(prune);  // bit k = prune[k]
+                prune[k] = __builtin_amdgcn_ballot_w64(x[s][k] > thr_scale * fmaf(c.B_pow[k], yin, y[s][k - 1]));
+            const uint32_t gone = pack_masks8(prune);  // bit k = decision k of this lane
             const uint32_t keep = on ? (gone ^ 0xffu) : 0u;
             pruned += on ? __popc(gone) : 0;
             const uint32_t word = quad_gather_bytes(keep, lane);
             // the four lanes of a quad hold the same word; in a FULL span all of them store it
             if (FULL || ((lane & 3) == 0 && on)) keep_mask[row * mask_words + (q0 >> 5)] = word;
-            if (APPLY && on) w[s].store_pruned(W, row_off + q0, prune);
+            if (APPLY && on) w[s].store_pruned_masks(W, row_off + q0, prune);
         }
     };
     // spans that end inside the row: only a wavefront that has a row takes the unpredicated code (the choice is
     // uniform per wavefront, and both versions meet the same barriers)
     const int full_spans = has_row ? (int)(in / span_cols) : 0;
+    // the full spans that are followed by another span request it without asking (no branch around the loads:
+    // the requested registers are then the loop's own, and nothing is copied at its end)
+    const int full_with_next = nspans > full_spans ? full_spans : full_spans - 1;
     int span = 0;
-    for (; span < full_spans; ++span) work(span, std::true_type());
-    for (; span < nspans; ++span) work(span, std::false_type());
+    for (; span < full_with_next; ++span) work(span, std::true_type(), std::true_type());
+    for (; span < full_spans; ++span) work(span, std::true_type(), std::false_type());
+    for (; span < nspans; ++span) work(span, std::false_type(), std::false_type());
 
     // counts: unconditional, so that every wavefront of the workgroup meets the barrier
     {
